@@ -1,0 +1,153 @@
+/*
+ * pme.h - C ABI of the expanded W4A4 linear layer for MI355X (gfx950).
+ *
+ * The operation is the inference path of post-training model expansion
+ * (paper Section 3): activations X (T x d) are rotated online by the expanded
+ * Hadamard matrix H_hat (d x d_e, the first d rows of a d_e x d_e Hadamard matrix
+ * scaled by gamma = 1/sqrt(d_e)), X_hat = X H_hat, quantized per token, and multiplied
+ * by the offline-expanded, quantized weights Q(W_hat), W_hat = H_hat^T W, so that the
+ * layer computes Q(X_hat) Q(W_hat) ~ X W.  Paper notation D, N, M, N' corresponds to
+ * T, d, d_e, N here.
+ *
+ * The Hadamard matrix of order d_e = b * 2^k is H = P_b (x) S_{2^k}: a Paley type-I
+ * block of order b (b - 1 prime and congruent to 3 mod 4; b = 1 for a pure power of
+ * two) Kronecker the natural-order Sylvester matrix; matrix index i = a * 2^k + c.
+ * The paper leaves the construction open ("a deterministic Hadamard matrix",
+ * Section 4); pme_base_block exports the block actually used.
+ *
+ * Conventions shared by every entry point unless stated otherwise:
+ *  - Pointers named in the comments as DEVICE are HIP device memory owned by the
+ *    caller.  The library never allocates, frees or synchronises; every call only
+ *    enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = default
+ *    stream) and returns.
+ *  - Arguments are validated on the host before any HIP call.  A status other than
+ *    PME_OK means nothing was launched (PME_ERR_HIP excepted: a launch was refused by
+ *    the runtime).  No C++ exception crosses this boundary.
+ *  - Packed int4: byte j/2 of a row holds code j (even j) in its low nibble and code
+ *    j+1 in its high nibble, each a 4-bit two's-complement integer (unsigned 0..15 for
+ *    the asymmetric activation variant).
+ *  - Rows of packed codes are dense: the row pitch is d_e / 2 bytes.
+ *  - Outputs must not alias inputs.
+ */
+#ifndef PME_H
+#define PME_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PME_OK = 0,
+    PME_ERR_NULL = 1,               /* a required pointer is NULL */
+    PME_ERR_SHAPE = 2,              /* negative / inconsistent sizes, d > d_e, odd d_e, pitch too small */
+    PME_ERR_UNSUPPORTED_ORDER = 3,  /* d_e is not b * 2^k with a supported base order b */
+    PME_ERR_ALIGN = 4,              /* pointer or pitch alignment requirement violated */
+    PME_ERR_WORKSPACE = 5,          /* workspace too small */
+    PME_ERR_DTYPE = 6,              /* unknown pme_dtype */
+    PME_ERR_HIP = 7,                /* the HIP runtime refused a launch */
+    PME_ERR_UNSUPPORTED_PATH = 8    /* the kernel path forced with pme_set_path cannot run this shape */
+} pme_status;
+
+typedef enum { PME_F32 = 0, PME_BF16 = 1 } pme_dtype;
+
+/* Kernel-path selector (test / benchmark hook, process-wide, not thread-safe). */
+typedef enum {
+    PME_PATH_AUTO = 0,     /* MFMA kernels where the shape allows, generic kernels otherwise */
+    PME_PATH_GENERIC = 1,  /* plain-ALU kernels for every shape */
+    PME_PATH_MFMA = 2      /* MFMA kernels or PME_ERR_UNSUPPORTED_PATH */
+} pme_path;
+
+/*
+ * Online expansion + rotation + per-token symmetric int4 quantization
+ * (Section 3: X_hat = X H_hat; Section 4: per-token activation quantizer, taken
+ * symmetric here: scale = absmax / 7, round half to even, codes in [-7, 7]).
+ *   x   DEVICE [T, d] row-major, element type xt, ldx elements between rows (ldx >= d).
+ *   qx  DEVICE out [T, d_e / 2] packed int4 codes.   sx  DEVICE out [T] fp32 scales
+ *       (x_hat[t][j] ~ sx[t] * code[t][j]; an all-zero token gets scale 1, codes 0).
+ * Alignment: x to its element size, qx to 4 bytes (16 for the MFMA path), sx to 4.
+ * T == 0 is a no-op returning PME_OK.
+ */
+pme_status pme_hadamard_expand_quant(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                                     int64_t d_e, uint8_t* qx, float* sx, void* stream);
+
+/*
+ * Same rotation, per-token asymmetric uint4 quantization (the paper's Section 4 setting):
+ * lo = min(min_j, 0), hi = max(max_j, 0), scale = (hi - lo) / 15, zero point
+ * z = rne(-lo / scale) in [0, 15], code = clamp(rne(x / scale) + z, 0, 15).
+ *   zx  DEVICE out [T] int32 zero points.  Other arguments as above (codes are unsigned).
+ */
+pme_status pme_hadamard_expand_quant_asym(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                                          int64_t d_e, uint8_t* qx, float* sx, int32_t* zx, void* stream);
+
+/*
+ * int4 x int4 GEMM with fused dequantisation (Section 3: Q(X_hat) Q(W_hat); Section 4:
+ * per-token activation scale, per-output-channel weight scale):
+ *   y[t][n] = bf16( (sum_j qx[t][j] * qw[n][j]) * sx[t] * sw[n] ).
+ *   qx DEVICE [T, d_e/2], sx DEVICE [T]; qw DEVICE [N, d_e/2] (one row of d_e codes per
+ *   output channel, i.e. the transpose of the paper's W_hat), sw DEVICE [N].
+ *   y  DEVICE out [T, N] bf16 row-major, ldy elements between rows (ldy >= N).
+ * The sum is exact int32 (|sum| <= 64 * d_e).  Alignment: qx, qw to 4 bytes (16 for the
+ * MFMA path), y to 2 bytes.  T == 0 or N == 0 is a no-op.
+ */
+pme_status pme_w4a4_gemm(const uint8_t* qx, const float* sx, const uint8_t* qw, const float* sw,
+                         int64_t T, int64_t d_e, int64_t N, void* y_bf16, int64_t ldy, void* stream);
+
+/*
+ * Asymmetric-activation variant: codes qx are unsigned with zero point zx[t];
+ *   y[t][n] = bf16( (sum_j qx[t][j] qw[n][j] - zx[t] * wsum[n]) * sx[t] * sw[n] ),
+ *   wsum DEVICE [N] int32 = sum_j qw[n][j] (see pme_weight_rowsum).
+ */
+pme_status pme_w4a4_gemm_asym(const uint8_t* qx, const float* sx, const int32_t* zx, const uint8_t* qw,
+                              const float* sw, const int32_t* wsum, int64_t T, int64_t d_e, int64_t N,
+                              void* y_bf16, int64_t ldy, void* stream);
+
+/* wsum[n] = sum_j qw[n][j] for packed signed weight codes.  qw DEVICE [N, d_e/2], wsum DEVICE out [N]. */
+pme_status pme_weight_rowsum(const uint8_t* qw, int64_t N, int64_t d_e, int32_t* wsum, void* stream);
+
+/*
+ * The whole expanded layer in one call: pme_hadamard_expand_quant followed by
+ * pme_w4a4_gemm, the codes and scales passing through `workspace`
+ * (DEVICE, 256-byte aligned, at least pme_workspace_bytes(T, d, d_e, N) bytes).
+ */
+pme_status pme_expanded_linear(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                               int64_t d_e, const uint8_t* qw, const float* sw, int64_t N,
+                               void* y_bf16, int64_t ldy, void* workspace, size_t workspace_bytes,
+                               void* stream);
+
+/* Bytes of workspace pme_expanded_linear needs (0 on invalid sizes). */
+size_t pme_workspace_bytes(int64_t T, int64_t d, int64_t d_e, int64_t N);
+
+/* ---- parity / debug exports ---- */
+
+/* X_hat itself (gamma applied), fp32: xhat DEVICE out [T, d_e] dense. */
+pme_status pme_hadamard_expand_f32(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                                   int64_t d_e, float* xhat, void* stream);
+
+/* The raw int32 accumulators of the GEMM: acc DEVICE out [T, N] dense. */
+pme_status pme_w4a4_gemm_i32(const uint8_t* qx, const uint8_t* qw, int64_t T, int64_t d_e, int64_t N,
+                             int32_t* acc, void* stream);
+
+/* d_e = b * 2^k with the smallest supported b; HOST pointers.  PME_ERR_UNSUPPORTED_ORDER if none. */
+pme_status pme_factor_order(int64_t d_e, int32_t* b, int32_t* k);
+
+/* The +-1 Paley block of order b, row-major b x b, written to HOST memory out_bxb. */
+pme_status pme_base_block(int64_t b, int8_t* out_bxb);
+
+/* ---- measurement helpers ---- */
+
+/* Plain device copy of `bytes` (multiple of 16) from src to dst, both DEVICE and 16-byte aligned:
+ * the known-size kernel used to calibrate the profiler's HBM byte counters. */
+pme_status pme_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+void pme_set_path(pme_path p);
+pme_path pme_get_path(void);
+const char* pme_status_string(pme_status s);
+int pme_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PME_H */

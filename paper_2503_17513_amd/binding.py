@@ -1,0 +1,223 @@
+"""ctypes binding of libpme.so.  Same names as the C entry points (minus the pme_ prefix)."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libpme.so")
+
+PATH_AUTO, PATH_GENERIC, PATH_MFMA = 0, 1, 2
+F32, BF16 = 0, 1
+
+# Every symbol include/pme.h declares.
+EXPORTS = ("pme_hadamard_expand_quant", "pme_hadamard_expand_quant_asym", "pme_w4a4_gemm", "pme_w4a4_gemm_asym",
+           "pme_weight_rowsum", "pme_expanded_linear", "pme_workspace_bytes", "pme_hadamard_expand_f32",
+           "pme_w4a4_gemm_i32", "pme_factor_order", "pme_base_block", "pme_probe_copy", "pme_set_path",
+           "pme_get_path", "pme_status_string", "pme_version")
+
+
+class PmeError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__(f"{what}: status {status} ({lib().pme_status_string(status).decode()})")
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library; raises if it has not been built (no fallback path exists)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(f"{_LIB_PATH} is missing: build it with `python paper_2503_17513_amd/csrc/build.py` "
+                           "(or __graft_entry__.build()); there is no fallback implementation")
+    L = C.CDLL(_LIB_PATH)
+    i64, vp, sz, i32 = C.c_int64, C.c_void_p, C.c_size_t, C.c_int
+    L.pme_hadamard_expand_quant.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp]
+    L.pme_hadamard_expand_quant_asym.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp, vp]
+    L.pme_hadamard_expand_f32.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp]
+    L.pme_w4a4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, vp]
+    L.pme_w4a4_gemm_asym.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, vp, i64, vp]
+    L.pme_w4a4_gemm_i32.argtypes = [vp, vp, i64, i64, i64, vp, vp]
+    L.pme_weight_rowsum.argtypes = [vp, i64, i64, vp, vp]
+    L.pme_expanded_linear.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i64, vp, i64, vp, sz, vp]
+    L.pme_workspace_bytes.argtypes = [i64, i64, i64, i64]
+    L.pme_workspace_bytes.restype = sz
+    L.pme_factor_order.argtypes = [i64, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
+    L.pme_base_block.argtypes = [i64, vp]
+    L.pme_probe_copy.argtypes = [vp, vp, sz, vp]
+    L.pme_set_path.argtypes = [i32]
+    L.pme_set_path.restype = None
+    L.pme_get_path.restype = i32
+    L.pme_status_string.argtypes = [i32]
+    L.pme_status_string.restype = C.c_char_p
+    L.pme_version.restype = i32
+    for name in EXPORTS:
+        fn = getattr(L, name)
+        if fn.restype is C.c_int and name not in ("pme_get_path", "pme_version"):
+            fn.restype = C.c_int
+    _lib = L
+    return L
+
+
+def _check(status: int, what: str):
+    if status != 0:
+        raise PmeError(status, what)
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _dtype_code(x: torch.Tensor) -> int:
+    if x.dtype == torch.float32:
+        return F32
+    if x.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError(f"activations must be float32 or bfloat16, got {x.dtype}")
+
+
+def _dev(t: torch.Tensor, name: str):
+    if not t.is_cuda:
+        raise ValueError(f"{name} must be a device tensor")
+    return t.data_ptr()
+
+
+def version() -> int:
+    return lib().pme_version()
+
+
+def set_path(p: int) -> None:
+    lib().pme_set_path(int(p))
+
+
+def get_path() -> int:
+    return lib().pme_get_path()
+
+
+def factor_order(d_e: int) -> tuple[int, int]:
+    b, k = C.c_int32(), C.c_int32()
+    _check(lib().pme_factor_order(d_e, C.byref(b), C.byref(k)), "pme_factor_order")
+    return b.value, k.value
+
+
+def base_block(b: int) -> np.ndarray:
+    out = np.zeros((b, b), dtype=np.int8)
+    _check(lib().pme_base_block(b, out.ctypes.data), "pme_base_block")
+    return out
+
+
+def workspace_bytes(T: int, d: int, d_e: int, N: int) -> int:
+    return lib().pme_workspace_bytes(T, d, d_e, N)
+
+
+def _rows(x: torch.Tensor):
+    if x.dim() != 2 or x.stride(1) != 1:
+        raise ValueError("x must be [T, d] with unit stride along d")
+    return x.shape[0], x.shape[1], x.stride(0) if x.shape[0] > 1 else max(x.stride(0), x.shape[1])
+
+
+def hadamard_expand_quant(x: torch.Tensor, d_e: int, qx: torch.Tensor | None = None, sx: torch.Tensor | None = None):
+    T, d, ldx = _rows(x)
+    if qx is None:
+        qx = torch.empty((T, d_e // 2), dtype=torch.uint8, device=x.device)
+    if sx is None:
+        sx = torch.empty((T,), dtype=torch.float32, device=x.device)
+    _check(lib().pme_hadamard_expand_quant(_dev(x, "x"), _dtype_code(x), T, d, ldx, d_e, _dev(qx, "qx"),
+                                           _dev(sx, "sx"), _stream()), "pme_hadamard_expand_quant")
+    return qx, sx
+
+
+def hadamard_expand_quant_asym(x: torch.Tensor, d_e: int):
+    T, d, ldx = _rows(x)
+    qx = torch.empty((T, d_e // 2), dtype=torch.uint8, device=x.device)
+    sx = torch.empty((T,), dtype=torch.float32, device=x.device)
+    zx = torch.empty((T,), dtype=torch.int32, device=x.device)
+    _check(lib().pme_hadamard_expand_quant_asym(_dev(x, "x"), _dtype_code(x), T, d, ldx, d_e, qx.data_ptr(),
+                                                sx.data_ptr(), zx.data_ptr(), _stream()),
+           "pme_hadamard_expand_quant_asym")
+    return qx, sx, zx
+
+
+def hadamard_expand_f32(x: torch.Tensor, d_e: int) -> torch.Tensor:
+    T, d, ldx = _rows(x)
+    xhat = torch.empty((T, d_e), dtype=torch.float32, device=x.device)
+    _check(lib().pme_hadamard_expand_f32(_dev(x, "x"), _dtype_code(x), T, d, ldx, d_e, xhat.data_ptr(), _stream()),
+           "pme_hadamard_expand_f32")
+    return xhat
+
+
+def _gemm_shapes(qx, qw):
+    if qx.dtype != torch.uint8 or qw.dtype != torch.uint8 or not qx.is_contiguous() or not qw.is_contiguous():
+        raise ValueError("qx and qw must be contiguous uint8 tensors of packed codes")
+    if qx.shape[1] != qw.shape[1]:
+        raise ValueError("qx and qw disagree on d_e")
+    return qx.shape[0], qx.shape[1] * 2, qw.shape[0]
+
+
+def w4a4_gemm(qx, sx, qw, sw, y: torch.Tensor | None = None) -> torch.Tensor:
+    T, d_e, N = _gemm_shapes(qx, qw)
+    if y is None:
+        y = torch.empty((T, N), dtype=torch.bfloat16, device=qx.device)
+    _check(lib().pme_w4a4_gemm(_dev(qx, "qx"), _dev(sx, "sx"), _dev(qw, "qw"), _dev(sw, "sw"), T, d_e, N,
+                               _dev(y, "y"), y.stride(0) if T > 1 else max(y.stride(0), N), _stream()),
+           "pme_w4a4_gemm")
+    return y
+
+
+def w4a4_gemm_asym(qx, sx, zx, qw, sw, wsum) -> torch.Tensor:
+    T, d_e, N = _gemm_shapes(qx, qw)
+    y = torch.empty((T, N), dtype=torch.bfloat16, device=qx.device)
+    _check(lib().pme_w4a4_gemm_asym(qx.data_ptr(), sx.data_ptr(), zx.data_ptr(), qw.data_ptr(), sw.data_ptr(),
+                                    wsum.data_ptr(), T, d_e, N, y.data_ptr(), N, _stream()), "pme_w4a4_gemm_asym")
+    return y
+
+
+def w4a4_gemm_i32(qx, qw) -> torch.Tensor:
+    T, d_e, N = _gemm_shapes(qx, qw)
+    acc = torch.empty((T, N), dtype=torch.int32, device=qx.device)
+    _check(lib().pme_w4a4_gemm_i32(_dev(qx, "qx"), _dev(qw, "qw"), T, d_e, N, acc.data_ptr(), _stream()),
+           "pme_w4a4_gemm_i32")
+    return acc
+
+
+def weight_rowsum(qw: torch.Tensor) -> torch.Tensor:
+    N, kb = qw.shape
+    wsum = torch.empty((N,), dtype=torch.int32, device=qw.device)
+    _check(lib().pme_weight_rowsum(_dev(qw, "qw"), N, kb * 2, wsum.data_ptr(), _stream()), "pme_weight_rowsum")
+    return wsum
+
+
+def expanded_linear(x, d_e: int, qw, sw, y: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    T, d, ldx = _rows(x)
+    N = qw.shape[0]
+    if qw.shape[1] * 2 != d_e:
+        raise ValueError("qw must be [N, d_e / 2]")
+    need = workspace_bytes(T, d, d_e, N)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
+    if y is None:
+        y = torch.empty((T, N), dtype=torch.bfloat16, device=x.device)
+    _check(lib().pme_expanded_linear(_dev(x, "x"), _dtype_code(x), T, d, ldx, d_e, _dev(qw, "qw"), _dev(sw, "sw"), N,
+                                     _dev(y, "y"), y.stride(0) if T > 1 else max(y.stride(0), N),
+                                     _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
+                                     _stream()), "pme_expanded_linear")
+    return y
+
+
+def probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(lib().pme_probe_copy(_dev(src, "src"), _dev(dst, "dst"), nbytes, _stream()), "pme_probe_copy")
+
+
+def pack_int4_codes(codes: torch.Tensor) -> torch.Tensor:
+    """Input preparation (not part of the hot path): int8 codes [.., K] in [-8, 7] -> packed uint8 [.., K/2],
+    even index in the low nibble."""
+    u = (codes.to(torch.int16) & 0xF).to(torch.uint8)
+    return (u[..., 0::2] | (u[..., 1::2] << 4)).contiguous()

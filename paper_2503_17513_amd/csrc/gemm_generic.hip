@@ -1,0 +1,86 @@
+// Plain-ALU int4 x int4 GEMM with the dequantising epilogue: one thread per output element.
+// Covers every shape (any even d_e, ragged T and N); the fallback for shapes the MFMA kernel
+// does not take and the second implementation the tests cross-check it with.
+#include "pme_internal.h"
+
+namespace pme {
+namespace {
+
+__device__ __forceinline__ int sext4(uint32_t nib) { return ((int)(nib << 28)) >> 28; }
+
+template <bool ASYM>
+__global__ void __launch_bounds__(256)
+k_gemm_generic(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
+               const float* __restrict__ sx, const float* __restrict__ sw,
+               const int32_t* __restrict__ zx, const int32_t* __restrict__ wsum,
+               int T, int N, int kb, void* __restrict__ out, int64_t ldo, int out_i32) {
+    const int n = blockIdx.x * 16 + (threadIdx.x & 15);
+    const int t = blockIdx.y * 16 + (threadIdx.x >> 4);
+    if (n >= N || t >= T) return;
+    const uint8_t* ar = qx + (int64_t)t * kb;
+    const uint8_t* wr = qw + (int64_t)n * kb;
+    int acc = 0;
+    for (int p = 0; p < kb; ++p) {
+        const uint32_t av = ar[p], wv = wr[p];
+        const int a0 = ASYM ? (int)(av & 0xF) : sext4(av & 0xF);
+        const int a1 = ASYM ? (int)(av >> 4) : sext4(av >> 4);
+        acc += a0 * sext4(wv & 0xF) + a1 * sext4(wv >> 4);
+    }
+    if (ASYM) acc -= zx[t] * wsum[n];
+    if (out_i32) {
+        static_cast<int32_t*>(out)[(int64_t)t * ldo + n] = acc;
+    } else {
+        const float y = (float)acc * sx[t] * sw[n];
+        static_cast<uint16_t*>(out)[(int64_t)t * ldo + n] = f32_to_bf16_bits(y);
+    }
+}
+
+__global__ void __launch_bounds__(64)
+k_weight_rowsum(const uint8_t* __restrict__ qw, int kb, int32_t* __restrict__ wsum) {
+    const int n = blockIdx.x, lane = threadIdx.x;
+    const uint8_t* wr = qw + (int64_t)n * kb;
+    int s = 0;
+    for (int p = lane; p < kb; p += 64) {
+        const uint32_t wv = wr[p];
+        s += sext4(wv & 0xF) + sext4(wv >> 4);
+    }
+    for (int off = 32; off > 0; off >>= 1) s += __shfl_xor(s, off);
+    if (lane == 0) wsum[n] = s;
+}
+
+__global__ void __launch_bounds__(256)
+k_probe_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+}  // namespace
+
+pme_status launch_gemm_generic(const GemmArgs& a) {
+    dim3 grid((unsigned)((a.N + 15) / 16), (unsigned)((a.T + 15) / 16));
+    if ((a.T + 15) / 16 > 65535) return PME_ERR_UNSUPPORTED_PATH;
+    const int kb = (int)(a.d_e / 2);
+    if (a.zx)
+        hipLaunchKernelGGL(k_gemm_generic<true>, grid, dim3(256), 0, a.stream, a.qx, a.qw, a.sx, a.sw, a.zx,
+                           a.wsum, (int)a.T, (int)a.N, kb, a.y, a.ldy, a.out_i32 ? 1 : 0);
+    else
+        hipLaunchKernelGGL(k_gemm_generic<false>, grid, dim3(256), 0, a.stream, a.qx, a.qw, a.sx, a.sw, a.zx,
+                           a.wsum, (int)a.T, (int)a.N, kb, a.y, a.ldy, a.out_i32 ? 1 : 0);
+    return hip_status(hipGetLastError());
+}
+
+pme_status launch_weight_rowsum(const uint8_t* qw, int64_t N, int64_t d_e, int32_t* wsum, hipStream_t s) {
+    hipLaunchKernelGGL(k_weight_rowsum, dim3((unsigned)N), dim3(64), 0, s, qw, (int)(d_e / 2), wsum);
+    return hip_status(hipGetLastError());
+}
+
+pme_status launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL(k_probe_copy, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n16);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace pme

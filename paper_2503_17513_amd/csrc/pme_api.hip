@@ -1,0 +1,246 @@
+// C-ABI entry points: host-side validation and dispatch.  No HIP call is made before the
+// arguments have been accepted.
+#include "pme_internal.h"
+
+#include <atomic>
+
+namespace {
+
+std::atomic<int> g_path{PME_PATH_AUTO};
+
+// Base orders b = q + 1, q prime and congruent to 3 mod 4, with pairwise distinct odd parts,
+// so that d_e = b * 2^k has at most one solution.  b = 1: plain power of two.
+const int kBaseOrders[] = {1, 12, 20, 60, 68, 72, 132, 140, 152};
+
+bool factor_order(int64_t d_e, int* b, int* k) {
+    if (d_e <= 0) return false;
+    for (int cand : kBaseOrders) {
+        if (d_e % cand) continue;
+        int64_t c = d_e / cand;
+        if ((c & (c - 1)) != 0) continue;
+        int kk = 0;
+        while ((int64_t(1) << kk) < c) ++kk;
+        *b = cand;
+        *k = kk;
+        return true;
+    }
+    return false;
+}
+
+bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
+
+pme_status check_rotate(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx, int64_t d_e,
+                        int* b, int* k) {
+    if (xt != PME_F32 && xt != PME_BF16) return PME_ERR_DTYPE;
+    if (T < 0 || d <= 0 || d_e <= 0 || d > d_e || ldx < d || (d_e & 1)) return PME_ERR_SHAPE;
+    if (T > 0x7FFFFFFF || d_e > (int64_t(1) << 20)) return PME_ERR_SHAPE;
+    if (!factor_order(d_e, b, k)) return PME_ERR_UNSUPPORTED_ORDER;
+    if (T > 0 && !x) return PME_ERR_NULL;
+    if (!aligned(x, xt == PME_F32 ? 4 : 2)) return PME_ERR_ALIGN;
+    return PME_OK;
+}
+
+pme_status run_rotate(const pme::RotateArgs& a) {
+    if (a.T == 0) return PME_OK;
+    int path = g_path.load();
+    if (path != PME_PATH_GENERIC) {
+        pme_status s = pme::launch_rotate_mfma(a);
+        if (s != PME_ERR_UNSUPPORTED_PATH || path == PME_PATH_MFMA) return s;
+    }
+    return pme::launch_rotate_generic(a);
+}
+
+pme_status check_gemm(const uint8_t* qx, const uint8_t* qw, int64_t T, int64_t d_e, int64_t N) {
+    if (T < 0 || N < 0 || d_e <= 0 || (d_e & 1)) return PME_ERR_SHAPE;
+    if (T > 0x7FFFFFFF || N > 0x7FFFFFFF || d_e > (int64_t(1) << 20)) return PME_ERR_SHAPE;
+    if (T > 0 && N > 0 && (!qx || !qw)) return PME_ERR_NULL;
+    if (!aligned(qx, 4) || !aligned(qw, 4)) return PME_ERR_ALIGN;
+    return PME_OK;
+}
+
+pme_status run_gemm(const pme::GemmArgs& a) {
+    if (a.T == 0 || a.N == 0) return PME_OK;
+    int path = g_path.load();
+    if (path != PME_PATH_GENERIC) {
+        pme_status s = pme::launch_gemm_mfma(a);
+        if (s != PME_ERR_UNSUPPORTED_PATH || path == PME_PATH_MFMA) return s;
+    }
+    return pme::launch_gemm_generic(a);
+}
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+extern "C" {
+#pragma GCC visibility push(default)
+
+pme_status pme_hadamard_expand_quant(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                                     int64_t d_e, uint8_t* qx, float* sx, void* stream) {
+    int b, k;
+    pme_status s = check_rotate(x, xt, T, d, ldx, d_e, &b, &k);
+    if (s != PME_OK) return s;
+    if (T > 0 && (!qx || !sx)) return PME_ERR_NULL;
+    if (!aligned(qx, 4) || !aligned(sx, 4)) return PME_ERR_ALIGN;
+    pme::RotateArgs a{x, xt, T, d, ldx, d_e, b, k, qx, sx, nullptr, nullptr, (hipStream_t)stream};
+    return run_rotate(a);
+}
+
+pme_status pme_hadamard_expand_quant_asym(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                                          int64_t d_e, uint8_t* qx, float* sx, int32_t* zx, void* stream) {
+    int b, k;
+    pme_status s = check_rotate(x, xt, T, d, ldx, d_e, &b, &k);
+    if (s != PME_OK) return s;
+    if (T > 0 && (!qx || !sx || !zx)) return PME_ERR_NULL;
+    if (!aligned(qx, 4) || !aligned(sx, 4) || !aligned(zx, 4)) return PME_ERR_ALIGN;
+    pme::RotateArgs a{x, xt, T, d, ldx, d_e, b, k, qx, sx, zx, nullptr, (hipStream_t)stream};
+    return run_rotate(a);
+}
+
+pme_status pme_hadamard_expand_f32(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                                   int64_t d_e, float* xhat, void* stream) {
+    int b, k;
+    pme_status s = check_rotate(x, xt, T, d, ldx, d_e, &b, &k);
+    if (s != PME_OK) return s;
+    if (T > 0 && !xhat) return PME_ERR_NULL;
+    if (!aligned(xhat, 4)) return PME_ERR_ALIGN;
+    pme::RotateArgs a{x, xt, T, d, ldx, d_e, b, k, nullptr, nullptr, nullptr, xhat, (hipStream_t)stream};
+    return run_rotate(a);
+}
+
+pme_status pme_w4a4_gemm(const uint8_t* qx, const float* sx, const uint8_t* qw, const float* sw,
+                         int64_t T, int64_t d_e, int64_t N, void* y_bf16, int64_t ldy, void* stream) {
+    pme_status s = check_gemm(qx, qw, T, d_e, N);
+    if (s != PME_OK) return s;
+    if (ldy < N) return PME_ERR_SHAPE;
+    if (T > 0 && N > 0 && (!sx || !sw || !y_bf16)) return PME_ERR_NULL;
+    if (!aligned(sx, 4) || !aligned(sw, 4) || !aligned(y_bf16, 2)) return PME_ERR_ALIGN;
+    pme::GemmArgs a{qx, qw, sx, sw, nullptr, nullptr, T, d_e, N, y_bf16, ldy, false, (hipStream_t)stream};
+    return run_gemm(a);
+}
+
+pme_status pme_w4a4_gemm_asym(const uint8_t* qx, const float* sx, const int32_t* zx, const uint8_t* qw,
+                              const float* sw, const int32_t* wsum, int64_t T, int64_t d_e, int64_t N,
+                              void* y_bf16, int64_t ldy, void* stream) {
+    pme_status s = check_gemm(qx, qw, T, d_e, N);
+    if (s != PME_OK) return s;
+    if (ldy < N) return PME_ERR_SHAPE;
+    if (T > 0 && N > 0 && (!sx || !sw || !y_bf16 || !zx || !wsum)) return PME_ERR_NULL;
+    if (!aligned(sx, 4) || !aligned(sw, 4) || !aligned(y_bf16, 2) || !aligned(zx, 4) || !aligned(wsum, 4))
+        return PME_ERR_ALIGN;
+    pme::GemmArgs a{qx, qw, sx, sw, zx, wsum, T, d_e, N, y_bf16, ldy, false, (hipStream_t)stream};
+    return run_gemm(a);
+}
+
+pme_status pme_w4a4_gemm_i32(const uint8_t* qx, const uint8_t* qw, int64_t T, int64_t d_e, int64_t N,
+                             int32_t* acc, void* stream) {
+    pme_status s = check_gemm(qx, qw, T, d_e, N);
+    if (s != PME_OK) return s;
+    if (T > 0 && N > 0 && !acc) return PME_ERR_NULL;
+    if (!aligned(acc, 4)) return PME_ERR_ALIGN;
+    pme::GemmArgs a{qx, qw, nullptr, nullptr, nullptr, nullptr, T, d_e, N, acc, N, true, (hipStream_t)stream};
+    return run_gemm(a);
+}
+
+pme_status pme_weight_rowsum(const uint8_t* qw, int64_t N, int64_t d_e, int32_t* wsum, void* stream) {
+    if (N < 0 || d_e <= 0 || (d_e & 1) || N > 0x7FFFFFFF || d_e > (int64_t(1) << 20)) return PME_ERR_SHAPE;
+    if (N > 0 && (!qw || !wsum)) return PME_ERR_NULL;
+    if (!aligned(qw, 4) || !aligned(wsum, 4)) return PME_ERR_ALIGN;
+    if (N == 0) return PME_OK;
+    return pme::launch_weight_rowsum(qw, N, d_e, wsum, (hipStream_t)stream);
+}
+
+size_t pme_workspace_bytes(int64_t T, int64_t d, int64_t d_e, int64_t N) {
+    (void)N;
+    if (T < 0 || d <= 0 || d_e <= 0 || d > d_e || (d_e & 1)) return 0;
+    // packed codes [T, d_e/2] then scales [T], each region 256-byte aligned
+    return round_up((size_t)T * (size_t)(d_e / 2), 256) + round_up((size_t)T * sizeof(float), 256);
+}
+
+pme_status pme_expanded_linear(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                               int64_t d_e, const uint8_t* qw, const float* sw, int64_t N,
+                               void* y_bf16, int64_t ldy, void* workspace, size_t workspace_bytes,
+                               void* stream) {
+    int b, k;
+    pme_status s = check_rotate(x, xt, T, d, ldx, d_e, &b, &k);
+    if (s != PME_OK) return s;
+    if (N < 0 || N > 0x7FFFFFFF || ldy < N) return PME_ERR_SHAPE;
+    if (T > 0 && N > 0 && (!qw || !sw || !y_bf16)) return PME_ERR_NULL;
+    if (!aligned(qw, 4) || !aligned(sw, 4) || !aligned(y_bf16, 2)) return PME_ERR_ALIGN;
+    size_t need = pme_workspace_bytes(T, d, d_e, N);
+    if (T > 0 && !workspace) return PME_ERR_NULL;
+    if (!aligned(workspace, 256)) return PME_ERR_ALIGN;
+    if (workspace_bytes < need) return PME_ERR_WORKSPACE;
+    if (T == 0 || N == 0) return PME_OK;
+    uint8_t* qx = static_cast<uint8_t*>(workspace);
+    float* sx = reinterpret_cast<float*>(qx + round_up((size_t)T * (size_t)(d_e / 2), 256));
+    pme::RotateArgs ra{x, xt, T, d, ldx, d_e, b, k, qx, sx, nullptr, nullptr, (hipStream_t)stream};
+    s = run_rotate(ra);
+    if (s != PME_OK) return s;
+    pme::GemmArgs ga{qx, qw, sx, sw, nullptr, nullptr, T, d_e, N, y_bf16, ldy, false, (hipStream_t)stream};
+    return run_gemm(ga);
+}
+
+pme_status pme_factor_order(int64_t d_e, int32_t* b, int32_t* k) {
+    if (!b || !k) return PME_ERR_NULL;
+    int bb, kk;
+    if (!factor_order(d_e, &bb, &kk)) return PME_ERR_UNSUPPORTED_ORDER;
+    *b = bb;
+    *k = kk;
+    return PME_OK;
+}
+
+pme_status pme_base_block(int64_t b, int8_t* out) {
+    if (!out) return PME_ERR_NULL;
+    bool known = false;
+    for (int cand : kBaseOrders) known = known || (cand == b);
+    if (!known) return PME_ERR_UNSUPPORTED_ORDER;
+    if (b == 1) { out[0] = 1; return PME_OK; }
+    const int q = (int)b - 1;
+    // quadratic character of GF(q) by marking the squares
+    int8_t chi[256];
+    for (int i = 0; i < q; ++i) chi[i] = -1;
+    chi[0] = 0;
+    for (int i = 1; i < q; ++i) chi[(i * i) % q] = 1;
+    for (int a = 0; a < b; ++a)
+        for (int ap = 0; ap < b; ++ap) {
+            int v;
+            if (a == 0) v = 1;
+            else if (ap == 0) v = -1;
+            else if (a == ap) v = 1;
+            else v = chi[((a - ap) % q + q) % q];
+            out[a * b + ap] = (int8_t)v;
+        }
+    return PME_OK;
+}
+
+pme_status pme_probe_copy(const void* src, void* dst, size_t bytes, void* stream) {
+    if (!src || !dst) return PME_ERR_NULL;
+    if (bytes % 16) return PME_ERR_SHAPE;
+    if (!aligned(src, 16) || !aligned(dst, 16)) return PME_ERR_ALIGN;
+    if (bytes == 0) return PME_OK;
+    return pme::launch_probe_copy(src, dst, bytes, (hipStream_t)stream);
+}
+
+void pme_set_path(pme_path p) { g_path.store((int)p); }
+pme_path pme_get_path(void) { return (pme_path)g_path.load(); }
+
+const char* pme_status_string(pme_status s) {
+    switch (s) {
+        case PME_OK: return "ok";
+        case PME_ERR_NULL: return "null pointer";
+        case PME_ERR_SHAPE: return "bad shape";
+        case PME_ERR_UNSUPPORTED_ORDER: return "unsupported Hadamard order";
+        case PME_ERR_ALIGN: return "misaligned pointer or pitch";
+        case PME_ERR_WORKSPACE: return "workspace too small";
+        case PME_ERR_DTYPE: return "unknown dtype";
+        case PME_ERR_HIP: return "HIP launch failed";
+        case PME_ERR_UNSUPPORTED_PATH: return "forced kernel path does not cover this shape";
+    }
+    return "unknown status";
+}
+
+int pme_version(void) { return 100; }
+
+#pragma GCC visibility pop
+}  // extern "C"

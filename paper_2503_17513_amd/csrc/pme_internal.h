@@ -1,0 +1,64 @@
+// Internal declarations shared by the translation units of libpme (not installed).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "../../include/pme.h"
+
+namespace pme {
+
+struct RotateArgs {
+    const void* x;
+    pme_dtype xt;
+    int64_t T, d, ldx, d_e;
+    int b, k;            // d_e = b * 2^k
+    uint8_t* qx;         // packed codes out (may be null when only xhat is wanted)
+    float* sx;           // scales out
+    int32_t* zx;         // zero points out (asymmetric quantizer) or null
+    float* xhat;         // fp32 rotated activations out (debug) or null
+    hipStream_t stream;
+};
+
+struct GemmArgs {
+    const uint8_t* qx;
+    const uint8_t* qw;
+    const float* sx;     // null for the int32 debug output
+    const float* sw;
+    const int32_t* zx;   // asymmetric: zero points and weight row sums, else null
+    const int32_t* wsum;
+    int64_t T, d_e, N;
+    void* y;             // bf16 [T, ldy] or int32 [T, N]
+    int64_t ldy;
+    bool out_i32;
+    hipStream_t stream;
+};
+
+// Each launcher returns PME_ERR_UNSUPPORTED_PATH when the shape is outside what its kernels cover.
+pme_status launch_rotate_generic(const RotateArgs& a);
+pme_status launch_rotate_mfma(const RotateArgs& a);
+pme_status launch_gemm_generic(const GemmArgs& a);
+pme_status launch_gemm_mfma(const GemmArgs& a);
+pme_status launch_weight_rowsum(const uint8_t* qw, int64_t N, int64_t d_e, int32_t* wsum, hipStream_t s);
+pme_status launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+
+inline pme_status hip_status(hipError_t e) { return e == hipSuccess ? PME_OK : PME_ERR_HIP; }
+
+// Round-to-nearest-even float -> bf16 bits (finite inputs; NaN stays NaN).
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+// Entry P[a][ap] of the Paley type-I block I + [[0, 1^T], [-1, Q]], Q[i][j] = chi((i - j) mod q),
+// given the table chi[0..q-1] of the quadratic character.  b = q + 1.
+__device__ __forceinline__ int paley_entry(const signed char* chi, int q, int a, int ap) {
+    if (a == 0) return 1;
+    if (ap == 0) return -1;
+    if (a == ap) return 1;
+    int dlt = a - ap;
+    if (dlt < 0) dlt += q;
+    return chi[dlt];
+}
+
+}  // namespace pme

@@ -1,0 +1,442 @@
+// Rotate + quantize on the matrix cores: one workgroup per token.
+//
+// Per token (paper Section 3, X_hat = X H_hat, H = P_b (x) S_{2^k}, index i = a 2^k + c):
+//   1. the token's d inputs are loaded once, coalesced, and laid out in LDS as bf16 MFMA
+//      operand fragments of X~^T (rows c, contraction index a);
+//   2. base block: Z^T[c][a'] = sum_a X~[a][c] P[a][a'] with v_mfma_f32_16x16x32_bf16.  The +-1
+//      entries of P are exact in bf16, bf16 inputs are exact, fp32 inputs are split into three
+//      bf16 terms whose sum is exact, so every product is exact and accumulation is fp32.
+//      Only the ceil(d / 2^k) base rows that hold real inputs enter the contraction: the
+//      zero padding of the expansion is never read or materialised;
+//   3. FWHT along c in registers.  A lane owns one a' and 4 * (2^k / 16) values of c; two of
+//      the k butterfly stages live on lane bits 4 and 5 and are turned into register stages
+//      by v_permlane16_swap / v_permlane32_swap, which also leaves every lane with a
+//      contiguous run of 2^(k-2) outputs;
+//   4. per-token absmax (or min/max) by wavefront reduction, combined across waves in LDS;
+//   5. codes by one fused multiply-add with a rounding constant (round half to even),
+//      packed eight to a dword and stored in runs of 2^(k-3) bytes per lane.
+// Waves split the token by a' (16-wide tiles, TPW tiles per wave); the FWHT never crosses a'.
+#include "pme_internal.h"
+
+namespace pme {
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+
+constexpr int kMaxWaves = 10;   // b <= 152 -> at most 10 tiles of 16 columns
+
+template <int KLOG2> struct Layout {
+    static constexpr int NC = 1 << KLOG2;      // FWHT length
+    static constexpr int MT = NC / 16;         // 16-row MFMA tiles along c
+    static constexpr int NREG = MT * 4;        // values per lane per a'-tile
+    static constexpr int NBITS = KLOG2 - 2;    // register index bits
+    static constexpr int RUN = NC / 4;         // contiguous outputs per lane after the FWHT
+    // Position (within the lane's contiguous run) of register index idx after the FWHT.
+    // Before: idx bit 0,1 = c0,c1; idx bits 2.. = c4..c(k-1); lane bit 4 = c2, lane bit 5 = c3.
+    // After (k >= 6): the two top idx bits hold c2, c3; lane bits 4, 5 hold c(k-2), c(k-1).
+    // After (k == 5): idx bits = c0, c1, c2; lane bit 4 = c4, lane bit 5 = c3.
+    static constexpr int run_pos(int idx) {
+        if (KLOG2 == 5) return idx;
+        int lo = idx & 3;
+        int mid = (idx >> 2) & ((1 << (NBITS - 4)) - 1);     // c4 .. c(k-3)
+        int c2 = (idx >> (NBITS - 2)) & 1, c3 = (idx >> (NBITS - 1)) & 1;
+        return lo | (c2 << 2) | (c3 << 3) | (mid << 4);
+    }
+    static constexpr int reg_of_run_pos(int j) {
+        for (int idx = 0; idx < NREG; ++idx)
+            if (run_pos(idx) == j) return idx;
+        return -1;
+    }
+};
+
+__device__ __forceinline__ void swap16(float& r0, float& r1) {
+    // lane bit 4 <-> the register bit that distinguishes r0 / r1
+    u32x2 v = __builtin_amdgcn_permlane16_swap(__float_as_uint(r0), __float_as_uint(r1), false, false);
+    r0 = __uint_as_float(v.x);
+    r1 = __uint_as_float(v.y);
+}
+__device__ __forceinline__ void swap32(float& r0, float& r1) {
+    u32x2 v = __builtin_amdgcn_permlane32_swap(__float_as_uint(r0), __float_as_uint(r1), false, false);
+    r0 = __uint_as_float(v.x);
+    r1 = __uint_as_float(v.y);
+}
+
+template <int NREG, int BIT> __device__ __forceinline__ void butterfly(float (&v)[NREG]) {
+#pragma unroll
+    for (int i = 0; i < NREG; ++i)
+        if (!(i & (1 << BIT))) {
+            const float u = v[i], w = v[i | (1 << BIT)];
+            v[i] = u + w;
+            v[i | (1 << BIT)] = u - w;
+        }
+}
+template <int NREG, int BIT> __device__ __forceinline__ void lane_swap16(float (&v)[NREG]) {
+#pragma unroll
+    for (int i = 0; i < NREG; ++i)
+        if (!(i & (1 << BIT))) swap16(v[i], v[i | (1 << BIT)]);
+}
+template <int NREG, int BIT> __device__ __forceinline__ void lane_swap32(float (&v)[NREG]) {
+#pragma unroll
+    for (int i = 0; i < NREG; ++i)
+        if (!(i & (1 << BIT))) swap32(v[i], v[i | (1 << BIT)]);
+}
+
+template <int NREG, int BIT> struct RegStages {
+    static __device__ __forceinline__ void run(float (&v)[NREG]) {
+        butterfly<NREG, BIT>(v);
+        RegStages<NREG, BIT - 1>::run(v);
+    }
+};
+template <int NREG> struct RegStages<NREG, -1> {
+    static __device__ __forceinline__ void run(float (&)[NREG]) {}
+};
+
+template <int KLOG2> __device__ __forceinline__ void fwht_lane(float (&v)[Layout<KLOG2>::NREG]) {
+    using L = Layout<KLOG2>;
+    RegStages<L::NREG, L::NBITS - 1>::run(v);          // every c bit that starts in a register
+    if constexpr (KLOG2 == 5) {
+        lane_swap16<L::NREG, 2>(v);                    // idx bit 2: c4 -> c2
+        butterfly<L::NREG, 2>(v);
+        lane_swap32<L::NREG, 2>(v);                    // idx bit 2: c2 -> c3 (lane bit 5 now c2)
+        butterfly<L::NREG, 2>(v);
+        lane_swap32<L::NREG, 2>(v);                    // back: idx bit 2 = c2, lane bit 5 = c3
+    } else {
+        lane_swap16<L::NREG, L::NBITS - 2>(v);
+        lane_swap32<L::NREG, L::NBITS - 1>(v);
+        butterfly<L::NREG, L::NBITS - 2>(v);
+        butterfly<L::NREG, L::NBITS - 1>(v);
+    }
+}
+
+// First output column of this lane's run, for lane bits (l4, l5).
+template <int KLOG2> __device__ __forceinline__ int run_start(int l4, int l5) {
+    using L = Layout<KLOG2>;
+    if (KLOG2 == 5) return 8 * l5 + 16 * l4;
+    return L::RUN * (l4 + 2 * l5);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off));
+    return v;
+}
+__device__ __forceinline__ float wave_min(float v) {
+    for (int off = 32; off > 0; off >>= 1) v = fminf(v, __shfl_xor(v, off));
+    return v;
+}
+
+// bf16 bits of the truncation of f, and the exact remainder.
+__device__ __forceinline__ uint32_t split_hi(float f, float& rem) {
+    const uint32_t hi = __float_as_uint(f) & 0xFFFF0000u;
+    rem = f - __uint_as_float(hi);
+    return hi >> 16;
+}
+
+template <int KLOG2, int KS, int TPW, bool F32IN>
+__global__ void __launch_bounds__(64 * kMaxWaves)
+k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int d, int d_e, int b, double gamma,
+              uint8_t* __restrict__ qx, float* __restrict__ sx, int32_t* __restrict__ zx,
+              float* __restrict__ xhat) {
+    using L = Layout<KLOG2>;
+    constexpr int NC = L::NC, MT = L::MT, NREG = L::NREG;
+    constexpr int NS = F32IN ? 3 : 1;
+    constexpr int FRAG_BYTES = KS * MT * 64 * 16;    // one bf16 copy of the token in fragment order
+
+    extern __shared__ __align__(16) unsigned char smem[];
+    unsigned char* afrag = smem;                                        // NS * FRAG_BYTES
+    float* red = reinterpret_cast<float*>(smem + NS * FRAG_BYTES);     // 2 * kMaxWaves floats
+    signed char* chi = reinterpret_cast<signed char*>(red + 2 * kMaxWaves);
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int nwaves = blockDim.x >> 6;
+    const int64_t t = blockIdx.x;
+    const int q = b - 1;
+    const int rows = (d + NC - 1) >> KLOG2;          // base rows with real inputs (<= 32 * KS)
+    const int l15 = lane & 15, g = lane >> 4;
+
+    if (b > 1) {
+        for (int i = tid; i < q; i += blockDim.x) chi[i] = (i == 0) ? 0 : -1;
+        __syncthreads();
+        for (int i = 1 + tid; i < q; i += blockDim.x) chi[(i * i) % q] = 1;
+    }
+
+    // ---- 1. token -> LDS, in A-fragment order: fragment (ks, mt), slot (c % 16) + 16 g holds
+    //         the 8 values a = 32 ks + 8 g + e (e = 0..7) of column c = 16 mt + c % 16.
+    if constexpr (!F32IN) {
+        const uint16_t* xr = static_cast<const uint16_t*>(xv) + t * ldx;
+        constexpr int UNITS = KS * 4 * (NC / 2);
+        for (int u = tid; u < UNITS; u += blockDim.x) {
+            const int cp = u % (NC / 2), ag = u / (NC / 2);
+            const int c = 2 * cp, a0 = 8 * ag;
+            uint32_t w[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int i = (a0 + e) * NC + c;
+                w[e] = (i < d) ? *reinterpret_cast<const uint32_t*>(xr + i) : 0u;
+            }
+            u32x4 ev, od;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                ev[p] = (w[2 * p] & 0xFFFFu) | (w[2 * p + 1] << 16);
+                od[p] = (w[2 * p] >> 16) | (w[2 * p + 1] & 0xFFFF0000u);
+            }
+            const int ks = ag >> 2, gg = ag & 3, mt = c >> 4;
+            unsigned char* dst = afrag + ((size_t)((ks * MT + mt) * 64 + (c & 15) + 16 * gg)) * 16;
+            *reinterpret_cast<u32x4*>(dst) = ev;
+            *reinterpret_cast<u32x4*>(dst + 16) = od;
+        }
+    } else {
+        const float* xr = static_cast<const float*>(xv) + t * ldx;
+        constexpr int UNITS = KS * 4 * NC;
+        for (int u = tid; u < UNITS; u += blockDim.x) {
+            const int c = u % NC, ag = u / NC;
+            const int a0 = 8 * ag;
+            uint32_t h0[8], h1[8], h2[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int i = (a0 + e) * NC + c;
+                const float f = (i < d) ? xr[i] : 0.f;
+                float r1, r2, r3;
+                h0[e] = split_hi(f, r1);
+                h1[e] = split_hi(r1, r2);
+                h2[e] = split_hi(r2, r3);
+            }
+            const int ks = ag >> 2, gg = ag & 3, mt = c >> 4;
+            unsigned char* dst = afrag + ((size_t)((ks * MT + mt) * 64 + (c & 15) + 16 * gg)) * 16;
+            u32x4 p0, p1, p2;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                p0[p] = h0[2 * p] | (h0[2 * p + 1] << 16);
+                p1[p] = h1[2 * p] | (h1[2 * p + 1] << 16);
+                p2[p] = h2[2 * p] | (h2[2 * p + 1] << 16);
+            }
+            *reinterpret_cast<u32x4*>(dst) = p0;
+            *reinterpret_cast<u32x4*>(dst + FRAG_BYTES) = p1;
+            *reinterpret_cast<u32x4*>(dst + 2 * FRAG_BYTES) = p2;
+        }
+    }
+    __syncthreads();
+
+    // ---- 2. B fragments of P for this wave's a'-tiles: lane (a' = 16 tile + l15, g) holds
+    //         P[32 ks + 8 g + e][a'], e = 0..7, as bf16 (+-1, 0 outside the block or the real rows).
+    bf16x8 bfrag[TPW][KS];
+#pragma unroll
+    for (int ti = 0; ti < TPW; ++ti) {
+        const int ap = (wave * TPW + ti) * 16 + l15;
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            u32x4 pk;
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                uint32_t word = 0;
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int a = 32 * ks + 8 * g + 2 * p + h;
+                    uint32_t bits = 0;
+                    if (a < rows && a < b && ap < b) {
+                        const int sgn = (b > 1) ? paley_entry(chi, q, a, ap) : 1;
+                        bits = sgn > 0 ? 0x3F80u : 0xBF80u;
+                    }
+                    word |= bits << (16 * h);
+                }
+                pk[p] = word;
+            }
+            bfrag[ti][ks] = __builtin_bit_cast(bf16x8, pk);
+        }
+    }
+
+    // ---- 3. base block on the matrix cores
+    f32x4 acc[TPW][MT];
+#pragma unroll
+    for (int ti = 0; ti < TPW; ++ti)
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) acc[ti][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int sp = 0; sp < NS; ++sp) {
+                const u32x4 raw = *reinterpret_cast<const u32x4*>(
+                    afrag + (size_t)sp * FRAG_BYTES + ((size_t)((ks * MT + mt) * 64 + lane)) * 16);
+                const bf16x8 af = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+                for (int ti = 0; ti < TPW; ++ti)
+                    acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfrag[ti][ks], acc[ti][mt], 0, 0, 0);
+            }
+
+    // ---- 4. FWHT along c, in registers
+    float v[TPW][NREG];
+#pragma unroll
+    for (int ti = 0; ti < TPW; ++ti) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int r = 0; r < 4; ++r) v[ti][mt * 4 + r] = acc[ti][mt][r];
+        fwht_lane<KLOG2>(v[ti]);
+    }
+
+    const int l4 = (lane >> 4) & 1, l5 = lane >> 5;
+    const int c0 = run_start<KLOG2>(l4, l5);
+
+    if (xhat) {
+        const float gf = (float)gamma;
+#pragma unroll
+        for (int ti = 0; ti < TPW; ++ti) {
+            const int ap = (wave * TPW + ti) * 16 + l15;
+            if (ap < b) {
+                float* o = xhat + t * d_e + (int64_t)ap * NC + c0;
+#pragma unroll
+                for (int j = 0; j < L::RUN; ++j) o[j] = v[ti][L::reg_of_run_pos(j)] * gf;
+            }
+        }
+    }
+    if (!qx) return;
+
+    // ---- 5. per-token range
+    float hi = 0.f, lo = 0.f;
+#pragma unroll
+    for (int ti = 0; ti < TPW; ++ti)
+#pragma unroll
+        for (int i = 0; i < NREG; ++i) {
+            if (zx) {
+                hi = fmaxf(hi, v[ti][i]);
+                lo = fminf(lo, v[ti][i]);
+            } else {
+                hi = fmaxf(hi, fabsf(v[ti][i]));
+            }
+        }
+    hi = wave_max(hi);
+    if (zx) lo = wave_min(lo);
+    if (nwaves > 1) {
+        if (lane == 0) { red[wave] = hi; red[kMaxWaves + wave] = lo; }
+        __syncthreads();
+        for (int w = 0; w < nwaves; ++w) {
+            hi = fmaxf(hi, red[w]);
+            lo = fminf(lo, red[kMaxWaves + w]);
+        }
+    }
+
+    float s = 1.f, rinv = 0.f;
+    int z = 0;
+    if (!zx) {
+        if (hi > 0.f) {
+            s = (float)((double)hi * gamma / 7.0);
+            rinv = (float)(gamma / (double)s);
+        }
+        if (tid == 0) sx[t] = s;
+    } else {
+        if (hi > lo) {
+            s = (float)(((double)hi - (double)lo) * gamma / 15.0);
+            rinv = (float)(gamma / (double)s);
+            z = (int)rint(-(double)lo * gamma / (double)s);
+            z = min(15, max(0, z));
+        }
+        if (tid == 0) { sx[t] = s; zx[t] = z; }
+    }
+
+    // ---- 6. round, pack, store.  fma(u, rinv, 1.5 * 2^23) leaves rne(u * rinv) in the low
+    //         mantissa bits as a two's-complement integer.
+    const float magic = 12582912.f;
+#pragma unroll
+    for (int ti = 0; ti < TPW; ++ti) {
+        const int ap = (wave * TPW + ti) * 16 + l15;
+        uint32_t words[L::RUN / 8];
+#pragma unroll
+        for (int wd = 0; wd < L::RUN / 8; ++wd) {
+            uint32_t word = 0;
+#pragma unroll
+            for (int nb = 0; nb < 8; ++nb) {
+                const float f = __builtin_fmaf(v[ti][L::reg_of_run_pos(wd * 8 + nb)], rinv, magic);
+                int code = (int)(__float_as_uint(f) & 0x7FFFFFu) - 0x400000;   // exact integer
+                if (zx) code = min(15, max(0, code + z));
+                word |= ((uint32_t)code & 0xFu) << (4 * nb);
+            }
+            words[wd] = word;
+        }
+        if (ap < b) {
+            uint8_t* o = qx + t * (int64_t)(d_e / 2) + (((int64_t)ap * NC + c0) >> 1);
+            if constexpr (L::RUN / 8 == 1) {
+                *reinterpret_cast<uint32_t*>(o) = words[0];
+            } else if constexpr (L::RUN / 8 == 2) {
+                *reinterpret_cast<u32x2*>(o) = u32x2{words[0], words[1]};
+            } else {
+#pragma unroll
+                for (int wd = 0; wd < L::RUN / 8; wd += 4)
+                    *reinterpret_cast<u32x4*>(o + 4 * wd) = u32x4{words[wd], words[wd + 1], words[wd + 2], words[wd + 3]};
+            }
+        }
+    }
+}
+
+template <int KLOG2, int KS, int TPW, bool F32IN>
+pme_status launch_one(const RotateArgs& a, int nwaves) {
+    using L = Layout<KLOG2>;
+    constexpr int NS = F32IN ? 3 : 1;
+    const size_t lds = (size_t)NS * KS * L::MT * 64 * 16 + 2 * kMaxWaves * 4 + 256;
+    if (lds > 160 * 1024) return PME_ERR_UNSUPPORTED_PATH;
+    auto kern = k_rotate_mfma<KLOG2, KS, TPW, F32IN>;
+    if (lds > 64 * 1024) {
+        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+            return PME_ERR_HIP;
+    }
+    const double gamma = 1.0 / sqrt((double)a.d_e);
+    hipLaunchKernelGGL(kern, dim3((unsigned)a.T), dim3(64 * nwaves), lds, a.stream, a.x, a.ldx, (int)a.d,
+                       (int)a.d_e, a.b, gamma, a.qx, a.sx, a.zx, a.xhat);
+    return hip_status(hipGetLastError());
+}
+
+template <int KLOG2, bool F32IN, int TPW>
+pme_status dispatch_ks(const RotateArgs& a, int ks, int nwaves) {
+    switch (ks) {
+        case 1: return launch_one<KLOG2, 1, TPW, F32IN>(a, nwaves);
+        case 2: return launch_one<KLOG2, 2, TPW, F32IN>(a, nwaves);
+        case 3: return launch_one<KLOG2, 3, TPW, F32IN>(a, nwaves);
+        case 4: return launch_one<KLOG2, 4, TPW, F32IN>(a, nwaves);
+        case 5: return launch_one<KLOG2, 5, TPW, F32IN>(a, nwaves);
+    }
+    return PME_ERR_UNSUPPORTED_PATH;
+}
+
+}  // namespace
+
+pme_status launch_rotate_mfma(const RotateArgs& a) {
+    // Shapes covered: 32 <= 2^k <= 512; even d and even row pitch for bf16 input (pairs of inputs
+    // are loaded as dwords); 16-byte aligned code rows.
+    if (a.k < 5 || a.k > 9) return PME_ERR_UNSUPPORTED_PATH;
+    const bool f32 = a.xt == PME_F32;
+    if (!f32 && ((a.d & 1) || (a.ldx & 1) || (reinterpret_cast<uintptr_t>(a.x) & 3))) return PME_ERR_UNSUPPORTED_PATH;
+    if (a.qx && (reinterpret_cast<uintptr_t>(a.qx) & 15)) return PME_ERR_UNSUPPORTED_PATH;
+    const int nc = 1 << a.k;
+    const int rows = (int)((a.d + nc - 1) >> a.k);
+    const int ks = (rows + 31) / 32;
+    const int nt = (a.b + 15) / 16;
+    // a'-tiles per wave: bounded by registers (4 * 2^k / 16 accumulators per tile).
+    int tpw;
+    switch (a.k) {
+        case 5: tpw = 5; break;
+        case 6: tpw = 3; break;
+        case 7: tpw = 3; break;
+        case 8: tpw = 2; break;
+        default: tpw = 1; break;
+    }
+    // few tokens: spread a token over as many waves as it has tiles
+    if (a.T < 512 && a.k <= 8) tpw = 1;
+    const int nwaves = (nt + tpw - 1) / tpw;
+    if (nwaves > kMaxWaves) return PME_ERR_UNSUPPORTED_PATH;
+#define PME_ROT(K, TP)                                                             \
+    if (a.k == K && tpw == TP)                                                     \
+        return f32 ? dispatch_ks<K, true, TP>(a, ks, nwaves) : dispatch_ks<K, false, TP>(a, ks, nwaves);
+    PME_ROT(5, 5) PME_ROT(5, 1)
+    PME_ROT(6, 3) PME_ROT(6, 1)
+    PME_ROT(7, 3) PME_ROT(7, 1)
+    PME_ROT(8, 2) PME_ROT(8, 1)
+    PME_ROT(9, 1)
+#undef PME_ROT
+    return PME_ERR_UNSUPPORTED_PATH;
+}
+
+}  // namespace pme

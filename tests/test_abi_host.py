@@ -1,0 +1,134 @@
+"""Host-side tests of the C-ABI library that need no GPU: the library loads, exports every symbol the
+header declares, and rejects bad arguments with the documented status before any HIP call."""
+import ctypes as C
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+import paper_2503_17513_amd as pme
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, NULL, SHAPE, ORDER, ALIGN, WORKSPACE, DTYPE, HIP, PATH = range(9)
+FAKE = 0x10000   # a non-null, 64 KiB aligned address that is never dereferenced: every call below fails validation
+
+
+def test_header_symbols_are_exported():
+    with open(os.path.join(ROOT, "include", "pme.h")) as f:
+        text = f.read()
+    declared = set(re.findall(r"\b(pme_[a-z0-9_]+)\s*\(", text))
+    assert declared == set(pme.EXPORTS)
+    L = pme.lib()
+    for name in declared:
+        assert hasattr(L, name), name
+    assert pme.version() >= 100
+    assert L.pme_status_string(OK) == b"ok"
+    for s in range(1, 9):
+        assert L.pme_status_string(s) not in (b"ok", b"unknown status")
+
+
+def test_factor_order_matches_oracle():
+    for M in (80, 2176, 8704, 8448, 15360, 64, 8960, 9728, 10240, 12288, 18432, 24, 40):
+        assert pme.factor_order(M) == oracle.factor_order(M)
+    for bad in (7, 100, 19968, 22016, 0, -4):
+        with pytest.raises(pme.PmeError) as e:
+            pme.factor_order(bad)
+        assert e.value.status == ORDER
+
+
+def test_base_block_matches_oracle():
+    for b in oracle.SUPPORTED_BASE:
+        assert np.array_equal(pme.base_block(b), oracle.paley_block(b))
+    out = np.zeros((16, 16), np.int8)
+    assert pme.lib().pme_base_block(16, out.ctypes.data) == ORDER
+    assert pme.lib().pme_base_block(20, None) == NULL
+
+
+def test_rotate_argument_errors():
+    f = pme.lib().pme_hadamard_expand_quant
+    good = dict(x=FAKE, xt=1, T=4, d=64, ldx=64, d_e=80, qx=FAKE, sx=FAKE, stream=None)
+
+    def call(**kw):
+        a = dict(good, **kw)
+        return f(a["x"], a["xt"], a["T"], a["d"], a["ldx"], a["d_e"], a["qx"], a["sx"], a["stream"])
+
+    assert call(x=None) == NULL
+    assert call(qx=None) == NULL
+    assert call(sx=None) == NULL
+    assert call(xt=5) == DTYPE
+    assert call(T=-1) == SHAPE
+    assert call(d=0) == SHAPE
+    assert call(d=81) == SHAPE            # d > d_e
+    assert call(ldx=63) == SHAPE          # pitch smaller than d
+    assert call(d_e=81, d=64) == SHAPE    # odd d_e
+    assert call(d_e=100) == ORDER
+    assert call(d_e=19968, d=64) == ORDER
+    assert call(x=FAKE + 1) == ALIGN
+    assert call(xt=0, x=FAKE + 2) == ALIGN
+    assert call(qx=FAKE + 2) == ALIGN
+    assert call(sx=FAKE + 2) == ALIGN
+    assert call(T=0, x=None, qx=None, sx=None) == OK      # empty input: no-op
+
+
+def test_gemm_argument_errors():
+    f = pme.lib().pme_w4a4_gemm
+
+    def call(qx=FAKE, sx=FAKE, qw=FAKE, sw=FAKE, T=4, d_e=80, N=8, y=FAKE, ldy=8):
+        return f(qx, sx, qw, sw, T, d_e, N, y, ldy, None)
+
+    assert call(qx=None) == NULL
+    assert call(qw=None) == NULL
+    assert call(sx=None) == NULL
+    assert call(sw=None) == NULL
+    assert call(y=None) == NULL
+    assert call(T=-2) == SHAPE
+    assert call(N=-1) == SHAPE
+    assert call(d_e=0) == SHAPE
+    assert call(d_e=81) == SHAPE
+    assert call(ldy=7) == SHAPE
+    assert call(qx=FAKE + 1) == ALIGN
+    assert call(qw=FAKE + 3) == ALIGN
+    assert call(y=FAKE + 1) == ALIGN
+    assert call(T=0) == OK
+    assert call(N=0, ldy=0) == OK
+    g = pme.lib().pme_w4a4_gemm_i32
+    assert g(FAKE, FAKE, 4, 80, 8, None, None) == NULL
+    assert g(FAKE, FAKE, 4, 81, 8, FAKE, None) == SHAPE
+
+
+def test_expanded_linear_argument_errors():
+    f = pme.lib().pme_expanded_linear
+    need = pme.workspace_bytes(4, 64, 80, 8)
+    assert need == 256 + 256
+    assert pme.workspace_bytes(2048, 2048, 2176, 3072) == 2048 * 1088 + 2048 * 4
+    assert pme.workspace_bytes(4, 81, 80, 8) == 0
+
+    def call(x=FAKE, xt=1, T=4, d=64, ldx=64, d_e=80, qw=FAKE, sw=FAKE, N=8, y=FAKE, ldy=8, ws=FAKE, wsb=need):
+        return f(x, xt, T, d, ldx, d_e, qw, sw, N, y, ldy, ws, wsb, None)
+
+    assert call(wsb=need - 1) == WORKSPACE
+    assert call(ws=None) == NULL
+    assert call(ws=FAKE + 64) == ALIGN
+    assert call(qw=None) == NULL
+    assert call(d_e=100) == ORDER
+    assert call(xt=9) == DTYPE
+    assert call(ldy=4) == SHAPE
+    assert call(T=0, x=None, ws=None, wsb=0) == OK
+
+
+def test_probe_copy_errors():
+    f = pme.lib().pme_probe_copy
+    assert f(None, FAKE, 16, None) == NULL
+    assert f(FAKE, FAKE, 24, None) == SHAPE
+    assert f(FAKE + 8, FAKE, 32, None) == ALIGN
+    assert f(FAKE, FAKE, 0, None) == OK
+
+
+def test_binding_has_no_fallback():
+    # The binding refuses host tensors instead of computing anything itself.
+    import torch
+    x = torch.zeros(2, 64)
+    with pytest.raises(ValueError):
+        pme.hadamard_expand_quant(x, 80)

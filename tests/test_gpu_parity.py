@@ -1,0 +1,251 @@
+"""GPU parity tests: the HIP library, called through its C ABI, against the CPU oracle on the same
+seeded inputs.  Sizes are small enough for the oracle to finish in seconds yet span several MFMA
+tiles, several waves per token and ragged tails."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_17513_amd as pme
+from parity_util import check_bf16, check_codes, check_scales, check_xhat, to_device, unpack_gpu
+from workloads import custom_spec, make_workload
+
+pytestmark = pytest.mark.gpu
+
+GENERIC, MFMA = pme.PATH_GENERIC, pme.PATH_MFMA
+
+
+@pytest.fixture(autouse=True)
+def _reset_path():
+    yield
+    pme.set_path(pme.PATH_AUTO)
+
+
+# (name, T, d, d_e, in_dtype, paths)
+ROTATE_CASES = [
+    ("tiny_c1", 16, 64, 80, "f32", (GENERIC,)),
+    ("b68_k5", 37, 2048, 2176, "bf16", (GENERIC, MFMA)),
+    ("b68_k7", 9, 8192, 8704, "bf16", (GENERIC, MFMA)),
+    ("b132_k6", 8, 8192, 8448, "bf16", (GENERIC, MFMA)),
+    ("b60_k8", 5, 14336, 15360, "bf16", (GENERIC, MFMA)),
+    ("b68_k5_many_tokens", 700, 2048, 2176, "bf16", (MFMA,)),
+    ("b68_k7_many_tokens", 600, 8192, 8704, "bf16", (MFMA,)),
+    ("b60_k8_many_tokens", 520, 14336, 15360, "bf16", (MFMA,)),
+    ("ragged_d_inside_base_row", 6, 2000, 2176, "bf16", (GENERIC, MFMA)),
+    ("ragged_d_small", 6, 300, 2176, "bf16", (GENERIC, MFMA)),
+    ("odd_d", 4, 301, 2176, "bf16", (GENERIC,)),
+    ("f32_b68_k5", 7, 2048, 2176, "f32", (GENERIC, MFMA)),
+    ("f32_b132_k6", 3, 8192, 8448, "f32", (GENERIC, MFMA)),
+    ("pow2_ratio_one", 5, 256, 256, "bf16", (GENERIC, MFMA)),
+    ("pow2_padded", 5, 200, 256, "f32", (GENERIC, MFMA)),
+    ("pow2_k12", 3, 4096, 4096, "bf16", (GENERIC,)),
+    ("b12_k6", 4, 700, 768, "bf16", (GENERIC, MFMA)),
+    ("b20_k5", 4, 600, 640, "bf16", (GENERIC, MFMA)),
+    ("b72_k5", 4, 2100, 2304, "bf16", (GENERIC, MFMA)),
+    ("b140_k6", 3, 8192, 8960, "bf16", (GENERIC, MFMA)),
+    ("b152_k6", 3, 8192, 9728, "bf16", (GENERIC, MFMA)),
+    ("b20_k9", 3, 8192, 10240, "bf16", (GENERIC, MFMA)),
+    ("b12_k10", 2, 8192, 12288, "bf16", (GENERIC,)),
+    ("single_token", 1, 2048, 2176, "bf16", (GENERIC, MFMA)),
+]
+
+
+def _acts(T, d, d_e, in_dtype, seed=0):
+    spec = custom_spec(T, d, d_e, 8, in_dtype=in_dtype, act_dist="student_t3", outlier_frac=0.01,
+                       outlier_gain=50.0, seed=seed)
+    return make_workload(spec, weights=False).x
+
+
+@pytest.mark.parametrize("name,T,d,d_e,in_dtype,paths", ROTATE_CASES, ids=[c[0] for c in ROTATE_CASES])
+def test_rotate_and_quantize(name, T, d, d_e, in_dtype, paths):
+    x = _acts(T, d, d_e, in_dtype, seed=len(name))
+    x[0, : min(d, 7)] = 0.0
+    if T > 2:
+        x[1] = 0.0                      # an all-zero token
+        x[2] = 0.0
+        x[2, d // 2] = 1.0              # a one-hot token: every code is +-7
+    xd = to_device(x, in_dtype)
+    ref = oracle.rotate_structured(x, d_e)
+    q_ref, s_ref = oracle.quantize_sym_int4(ref)
+    for path in paths:
+        pme.set_path(path)
+        xhat = pme.hadamard_expand_f32(xd, d_e).cpu().numpy()
+        check_xhat(xhat, ref)
+        qx, sx = pme.hadamard_expand_quant(xd, d_e)
+        torch.cuda.synchronize()
+        check_scales(sx.cpu().numpy(), s_ref)
+        check_codes(unpack_gpu(qx), q_ref, ref, s_ref)
+        if T > 2:
+            assert sx[1].item() == 1.0 and int(qx[1].max()) == 0
+            assert np.all(np.abs(unpack_gpu(qx)[2]) == 7)
+
+
+@pytest.mark.parametrize("path", (GENERIC, MFMA))
+def test_rotate_strided_rows(path):
+    # ldx > d: rows of a wider buffer
+    T, d, d_e = 6, 2048, 2176
+    x = _acts(T, 2560, 2560, "bf16", seed=5)
+    xd_full = to_device(x, "bf16")
+    xd = xd_full[:, :d]
+    pme.set_path(path)
+    ref = oracle.rotate_structured(x[:, :d], d_e)
+    check_xhat(pme.hadamard_expand_f32(xd, d_e).cpu().numpy(), ref)
+
+
+ASYM_CASES = [("tiny", 16, 64, 80, "f32", (GENERIC,)), ("b68_k5", 9, 2048, 2176, "bf16", (GENERIC, MFMA)),
+              ("b60_k8", 4, 14336, 15360, "bf16", (GENERIC, MFMA))]
+
+
+@pytest.mark.parametrize("name,T,d,d_e,in_dtype,paths", ASYM_CASES, ids=[c[0] for c in ASYM_CASES])
+def test_rotate_and_quantize_asymmetric(name, T, d, d_e, in_dtype, paths):
+    x = _acts(T, d, d_e, in_dtype, seed=3) + np.float32(0.25)
+    if in_dtype == "bf16":
+        x = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    x[1] = 0.0
+    xd = to_device(x, in_dtype)
+    ref = oracle.rotate_structured(x, d_e)
+    q_ref, s_ref, z_ref = oracle.quantize_asym_int4(ref)
+    for path in paths:
+        pme.set_path(path)
+        qx, sx, zx = pme.hadamard_expand_quant_asym(xd, d_e)
+        check_scales(sx.cpu().numpy(), s_ref)
+        assert np.array_equal(zx.cpu().numpy(), z_ref)
+        check_codes(unpack_gpu(qx, signed=False), q_ref, ref, s_ref)
+
+
+# (name, T, N, d_e, paths)
+GEMM_CASES = [
+    ("tiny_c1", 16, 64, 80, (GENERIC,)),
+    ("ragged_generic", 77, 130, 262, (GENERIC,)),
+    ("one_k_step", 40, 72, 128, (GENERIC, MFMA)),
+    ("small_tile_ragged", 100, 200, 2176, (GENERIC, MFMA)),
+    ("tile_64x128", 500, 1100, 384, (MFMA,)),
+    ("tile_128x128", 1000, 2100, 256, (MFMA,)),
+    ("tile_128x192", 2048, 3072, 256, (MFMA,)),
+    ("tile_128x256", 2000, 4200, 256, (MFMA,)),
+    ("tile_256x256", 4000, 4100, 128, (MFMA,)),
+    ("single_row_col", 1, 1, 2176, (GENERIC, MFMA)),
+    ("decode_shape", 8, 2048, 8448, (GENERIC, MFMA)),
+]
+
+
+@pytest.mark.parametrize("name,T,N,d_e,paths", GEMM_CASES, ids=[c[0] for c in GEMM_CASES])
+def test_gemm_accumulators_and_epilogue(name, T, N, d_e, paths):
+    rng = np.random.default_rng(len(name) + T)
+    q = rng.integers(-7, 8, size=(T, d_e), dtype=np.int8)
+    qw = rng.integers(-8, 8, size=(N, d_e), dtype=np.int8)
+    if T > 1 and N > 1:
+        q[0] = 7                         # extreme rows: the accumulator reaches its bound
+        qw[0] = -8
+        qw[N - 1] = 7
+    sx = rng.uniform(0.01, 2.0, T).astype(np.float32)
+    sw = rng.uniform(0.001, 0.01, N).astype(np.float32)
+    acc_ref = oracle.int_gemm(q, qw)
+    y_ref = oracle.dequant_bf16(acc_ref, sx, sw)
+    qd = torch.from_numpy(oracle.pack_int4(q)).cuda()
+    wd = torch.from_numpy(oracle.pack_int4(qw)).cuda()
+    sxd, swd = torch.from_numpy(sx).cuda(), torch.from_numpy(sw).cuda()
+    for path in paths:
+        pme.set_path(path)
+        acc = pme.w4a4_gemm_i32(qd, wd).cpu().numpy()
+        assert np.array_equal(acc, acc_ref), f"path {path}: {np.count_nonzero(acc != acc_ref)} accumulators differ"
+        y = pme.w4a4_gemm(qd, sxd, wd, swd).to(torch.float32).cpu().numpy()
+        check_bf16(y, y_ref)
+
+
+@pytest.mark.parametrize("path", (GENERIC, MFMA))
+def test_gemm_asymmetric(path):
+    rng = np.random.default_rng(8)
+    T, N, d_e = 150, 260, 384
+    q = rng.integers(0, 16, size=(T, d_e), dtype=np.uint8)
+    z = rng.integers(0, 16, size=T).astype(np.int32)
+    qw = rng.integers(-8, 8, size=(N, d_e), dtype=np.int8)
+    sx = rng.uniform(0.01, 2.0, T).astype(np.float32)
+    sw = rng.uniform(0.001, 0.01, N).astype(np.float32)
+    y_ref = oracle.dequant_asym_bf16(oracle.int_gemm(q, qw), sx, z, qw, sw)
+    pme.set_path(path)
+    wd = torch.from_numpy(oracle.pack_int4(qw)).cuda()
+    wsum = pme.weight_rowsum(wd)
+    assert np.array_equal(wsum.cpu().numpy(), qw.astype(np.int64).sum(axis=1))
+    y = pme.w4a4_gemm_asym(torch.from_numpy(oracle.pack_int4(q)).cuda(), torch.from_numpy(sx).cuda(),
+                           torch.from_numpy(z).cuda(), wd, torch.from_numpy(sw).cuda(), wsum)
+    check_bf16(y.to(torch.float32).cpu().numpy(), y_ref)
+
+
+LAYER_CASES = [("C1", None), ("mid_b68_k5", (300, 2048, 2176, 520)), ("mid_b132_k6", (8, 8192, 8448, 2048)),
+               ("mid_b60_k8", (130, 14336, 15360, 260))]
+
+
+@pytest.mark.parametrize("name,shape", LAYER_CASES, ids=[c[0] for c in LAYER_CASES])
+def test_expanded_linear_end_to_end(name, shape):
+    if shape is None:
+        wl = make_workload("C1")
+    else:
+        T, d, d_e, N = shape
+        wl = make_workload(custom_spec(T, d, d_e, N, act_dist="student_t3", outlier_frac=0.005,
+                                       outlier_gain=100.0, seed=1))
+    sp = wl.spec
+    ref = oracle.expanded_linear(wl.x, sp.d_e, wl.qw, wl.sw)
+    xd = to_device(wl.x, sp.in_dtype)
+    wd = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+    assert np.array_equal(wd.cpu().numpy(), oracle.pack_int4(wl.qw))
+    swd = torch.from_numpy(wl.sw).cuda()
+    y = pme.expanded_linear(xd, sp.d_e, wd, swd).to(torch.float32).cpu().numpy()
+    # stage by stage with the library's own codes: the fused call must equal the chain of its parts
+    qx, sx = pme.hadamard_expand_quant(xd, sp.d_e)
+    q_gpu = unpack_gpu(qx)
+    nflip = check_codes(q_gpu, ref["qx"], ref["xhat"], ref["sx"])
+    check_scales(sx.cpu().numpy(), ref["sx"])
+    y_chain = oracle.dequant_bf16(oracle.int_gemm(q_gpu, wl.qw), sx.cpu().numpy(), wl.sw)
+    check_bf16(y, y_chain)
+    y2 = pme.w4a4_gemm(qx, sx, wd, swd).to(torch.float32).cpu().numpy()
+    assert np.array_equal(y, y2)
+    # against the oracle's own end-to-end output: tokens whose codes all agree meet the bf16 bound outright
+    same = np.all(q_gpu == ref["qx"], axis=1) & (sx.cpu().numpy() == ref["sx"])
+    if same.any():
+        check_bf16(y[same], ref["y"][same])
+    assert np.linalg.norm(y - ref["y"]) <= 2e-3 * np.linalg.norm(ref["y"])
+    assert nflip <= max(1, int(1e-4 * q_gpu.size))
+
+
+def test_run_twice_is_bit_identical():
+    wl = make_workload(custom_spec(257, 2048, 2176, 384, seed=4))
+    xd = to_device(wl.x, "bf16")
+    wd = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+    swd = torch.from_numpy(wl.sw).cuda()
+    outs = []
+    for _ in range(2):
+        qx, sx = pme.hadamard_expand_quant(xd, 2176)
+        acc = pme.w4a4_gemm_i32(qx, wd)
+        y = pme.expanded_linear(xd, 2176, wd, swd)
+        torch.cuda.synchronize()
+        outs.append((qx.clone(), sx.clone(), acc.clone(), y.clone()))
+    for a, b in zip(*outs):
+        assert torch.equal(a, b)
+
+
+def test_empty_inputs_are_no_ops():
+    x = torch.zeros((0, 64), dtype=torch.bfloat16, device="cuda")
+    qx, sx = pme.hadamard_expand_quant(x, 80)
+    assert qx.shape == (0, 40) and sx.shape == (0,)
+    qw = torch.zeros((0, 40), dtype=torch.uint8, device="cuda")
+    y = pme.w4a4_gemm(qx, sx, qw, torch.zeros(0, device="cuda"))
+    assert y.shape == (0, 0)
+
+
+def test_forced_mfma_path_refuses_unsupported_shape():
+    pme.set_path(MFMA)
+    x = torch.zeros((4, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(pme.PmeError) as e:
+        pme.hadamard_expand_quant(x, 80)      # 2^k = 4 is below the MFMA kernel's range
+    assert e.value.status == 8
+    q = torch.zeros((4, 40), dtype=torch.uint8, device="cuda")
+    with pytest.raises(pme.PmeError):
+        pme.w4a4_gemm_i32(q, q)               # d_e = 80 is not a multiple of 128
+
+
+def test_probe_copy():
+    src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.zeros_like(src)
+    pme.probe_copy(src, dst)
+    assert torch.equal(src, dst)
