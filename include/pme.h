@@ -142,6 +142,10 @@ pme_status pme_base_block(int64_t b, int8_t* out_bxb);
  * the known-size kernel used to calibrate the profiler's HBM byte counters. */
 pme_status pme_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 
+/* Tuning hook for benchmarks: force the MFMA GEMM's tile configuration (0 = choose from the shape;
+ * 1..10 = a fixed entry of the library's tile table).  Process-wide, not thread-safe. */
+void pme_set_gemm_tile(int id);
+
 void pme_set_path(pme_path p);
 pme_path pme_get_path(void);
 const char* pme_status_string(pme_status s);

@@ -5,12 +5,12 @@ arguments (torch tensors give device pointers and the current stream).  There is
 or PyTorch fallback: if the library has not been built, importing the binding functions
 raises.
 """
-from .binding import (PmeError, lib, version, set_path, get_path, factor_order, base_block, workspace_bytes,
+from .binding import (PmeError, lib, version, set_path, get_path, set_gemm_tile, factor_order, base_block, workspace_bytes,
                       hadamard_expand_quant, hadamard_expand_quant_asym, hadamard_expand_f32,
                       w4a4_gemm, w4a4_gemm_asym, w4a4_gemm_i32, weight_rowsum, expanded_linear,
                       probe_copy, pack_int4_codes, PATH_AUTO, PATH_GENERIC, PATH_MFMA, EXPORTS)
 
-__all__ = ["PmeError", "lib", "version", "set_path", "get_path", "factor_order", "base_block", "workspace_bytes",
+__all__ = ["PmeError", "lib", "version", "set_path", "get_path", "set_gemm_tile", "factor_order", "base_block", "workspace_bytes",
            "hadamard_expand_quant", "hadamard_expand_quant_asym", "hadamard_expand_f32", "w4a4_gemm",
            "w4a4_gemm_asym", "w4a4_gemm_i32", "weight_rowsum", "expanded_linear", "probe_copy",
            "pack_int4_codes", "PATH_AUTO", "PATH_GENERIC", "PATH_MFMA", "EXPORTS"]

@@ -16,7 +16,7 @@ F32, BF16 = 0, 1
 # Every symbol include/pme.h declares.
 EXPORTS = ("pme_hadamard_expand_quant", "pme_hadamard_expand_quant_asym", "pme_w4a4_gemm", "pme_w4a4_gemm_asym",
            "pme_weight_rowsum", "pme_expanded_linear", "pme_workspace_bytes", "pme_hadamard_expand_f32",
-           "pme_w4a4_gemm_i32", "pme_factor_order", "pme_base_block", "pme_probe_copy", "pme_set_path",
+           "pme_w4a4_gemm_i32", "pme_factor_order", "pme_base_block", "pme_probe_copy", "pme_set_path", "pme_set_gemm_tile",
            "pme_get_path", "pme_status_string", "pme_version")
 
 
@@ -53,6 +53,8 @@ def lib() -> C.CDLL:
     L.pme_base_block.argtypes = [i64, vp]
     L.pme_probe_copy.argtypes = [vp, vp, sz, vp]
     L.pme_set_path.argtypes = [i32]
+    L.pme_set_gemm_tile.argtypes = [i32]
+    L.pme_set_gemm_tile.restype = None
     L.pme_set_path.restype = None
     L.pme_get_path.restype = i32
     L.pme_status_string.argtypes = [i32]
@@ -95,6 +97,10 @@ def version() -> int:
 
 def set_path(p: int) -> None:
     lib().pme_set_path(int(p))
+
+
+def set_gemm_tile(tile_id: int) -> None:
+    lib().pme_set_gemm_tile(int(tile_id))
 
 
 def get_path() -> int:

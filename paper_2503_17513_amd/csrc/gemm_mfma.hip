@@ -3,16 +3,23 @@
 //   acc[t][n] = sum_j qx[t][j] qw[n][j]   (paper Section 3: Q(X_hat) Q(W_hat)),
 //   y[t][n]   = bf16(acc * sx[t] * sw[n]) (Section 4: per-token and per-channel scales).
 //
-// Both operands are K-contiguous packed int4.  A workgroup owns a BM x BN output tile and walks
-// K in steps of 128 codes (64 packed bytes per row).  Packed bytes go HBM -> registers -> LDS
-// (double buffered); a wave reads 16 packed bytes per lane (32 codes) with one ds_read_b128 and
-// unpacks them in registers into two int8 MFMA operands:
-//     even codes:  (w & 0x0F0F0F0F) << 4      odd codes:  w & 0xF0F0F0F0
-// A nibble moved to the top of a byte is 16 x its two's-complement value, so no sign extension
-// is needed; both operands carry the factor 16 and the int32 accumulator holds 256 x the exact
-// sum (|256 acc| <= 256 * 64 * d_e < 2^31 for d_e <= 2^17), removed in the epilogue.
-// The order in which codes meet inside an MFMA is the same permutation for both operands, which
-// an exact integer sum does not notice.
+// Both operands are K-contiguous packed int4.  A workgroup owns a BM x BN output tile and walks K
+// in steps of 128 codes (64 packed bytes per row).
+//  * HBM -> LDS: global_load_lds_dwordx4 (no registers, no VALU), three LDS stages, two K steps in
+//    flight while one is consumed.  The DMA instructions and the waits on them are issued from
+//    inline assembly, so that the compiler does not order LDS reads of one stage after DMA writes
+//    to another; the per-step barrier waits for LDS traffic only and for all but the newest
+//    stage's DMA (vmcnt counts in order).
+//  * LDS -> registers: one ds_read_b128 per lane brings 32 codes, unpacked in registers into two
+//    int8 MFMA operands:   even codes (w & 0x0F0F0F0F) << 4,   odd codes w & 0xF0F0F0F0.
+//    A nibble moved to the top of a byte is 16 x its two's-complement value: no sign extension.
+//    Both operands carry the factor 16, the int32 accumulator holds 256 x the exact sum
+//    (|256 acc| <= 256 * 64 * d_e < 2^31 for d_e <= 2^17), removed in the epilogue.  The order in
+//    which codes meet inside an MFMA is the same permutation for both operands, which an exact
+//    integer sum does not notice.
+//  * v_mfma_i32_32x32x32_i8 with the weight fragment as the first operand: a lane then owns one
+//    token and runs of four consecutive output channels, which the epilogue scales, rounds to
+//    bf16, transposes through LDS and stores as 16-byte row pieces.
 #include "pme_internal.h"
 
 namespace pme {
@@ -21,31 +28,58 @@ namespace {
 typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(16))) int i32x16;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+#define PME_AS1 __attribute__((address_space(1)))
+#define PME_AS3 __attribute__((address_space(3)))
 
 constexpr int kRowBytes = 64;     // packed bytes per tile row per K step (128 codes)
-constexpr int kThreads = 256;
+enum { MODE_BF16 = 0, MODE_ASYM = 1, MODE_I32 = 2 };
 
-// LDS swizzle: the 16-byte chunk kc (0..3) of tile row r is stored at chunk kc ^ swz(r), so that
-// the 16 or 32 rows read together by a ds_read_b128 spread over all banks.
+// LDS swizzle: the 16-byte chunk kc (0..3) of tile row r sits at chunk position kc ^ swz(r), so that
+// the rows read together by one ds_read_b128 spread over the banks.
 __device__ __forceinline__ int swz(int r) { return ((r >> 1) ^ (r >> 3)) & 3; }
 
-template <int BM, int BN, int WM, int WN, bool OUT_I32, bool ASYM>
-__global__ void __launch_bounds__(kThreads)
+// LDS-only barrier: DMA (vmcnt) stays in flight across it.
+// LDS-only barrier: DMA (counted by vmcnt) stays in flight across it.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+// 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base wave-uniform).
+// The statement overwrites M0, which the compiler reserves and does not keep values in; no other code in
+// this kernel makes the compiler emit an M0 use.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    const bf16x2 p = __builtin_convertvector(f32x2{a, b}, bf16x2);     // v_cvt_pk_bf16_f32: round half to even
+    return __builtin_bit_cast(uint32_t, p);
+}
+
+template <int BM, int BN, int WGM, int WGN, int MODE>
+__global__ void __launch_bounds__(64 * WGM * WGN)
 k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             const float* __restrict__ sx, const float* __restrict__ sw,
             const int32_t* __restrict__ zx, const int32_t* __restrict__ wsum,
-            int T, int N, int kb, void* __restrict__ out, int64_t ldo, int tiles_m, int tiles_n) {
-    static_assert((BM / WM) * (BN / WN) == kThreads / 64, "four waves");
-    constexpr int FM = WM / 32, FN = WN / 32;
+            int T, int N, int kb, void* __restrict__ out, int64_t ldo, int tiles_m, int tiles_n, int vec_store) {
+    constexpr int NW = WGM * WGN, NT = 64 * NW;
+    constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
     constexpr int ROWS = BM + BN;
-    constexpr int CHUNKS = ROWS * 4 / kThreads;     // 16-byte chunks each thread moves per K step
-    static_assert(ROWS * 4 % kThreads == 0, "tile rows");
+    constexpr int BLKS = ROWS / 16;               // 1 KB DMA blocks (16 rows) per stage
+    // DMA instructions per wave per stage.  Every wave issues the same number (the per-step wait counts
+    // on it); when the blocks do not divide evenly the surplus instructions repeat an earlier block.
+    constexpr int CH = (BLKS + NW - 1) / NW;
     constexpr int STAGE = ROWS * kRowBytes;
+    constexpr int SLAB = 32 * WN * 2;             // epilogue: one 32-token slab of the wave tile in bf16
+    static_assert(NW * SLAB <= 3 * STAGE, "epilogue staging must fit in the K-loop stages");
 
-    extern __shared__ __align__(16) unsigned char smem[];
+    extern __shared__ __align__(1024) unsigned char smem[];      // 3 stages
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int wm = wave / (BN / WN), wn = wave % (BN / WN);
+    const int wm = wave / WGN, wn = wave % WGN;
 
     // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tiles so
     // that tiles sharing rows of qx / qw share an L2.
@@ -55,19 +89,24 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     const int tm = tile / tiles_n, tn = tile % tiles_n;
     const int m0 = tm * BM, n0 = tn * BN;
 
-    // global source of each chunk this thread moves
-    const uint8_t* src[CHUNKS];
-    int dst_off[CHUNKS];
+    // DMA source of each 16-byte chunk this lane moves: block blk = wave + NW s covers tile rows
+    // 16 blk .. 16 blk + 15; lane L writes chunk position L % 4 of row 16 blk + L / 4.
+    const uint8_t* src[CH];
 #pragma unroll
-    for (int i = 0; i < CHUNKS; ++i) {
-        const int cid = tid + kThreads * i;
-        const int r = cid >> 2, kc = cid & 3;
-        const uint8_t* base;
-        if (r < BM) base = qx + (int64_t)min(m0 + r, T - 1) * kb;
-        else base = qw + (int64_t)min(n0 + r - BM, N - 1) * kb;
-        src[i] = base + kc * 16;
-        dst_off[i] = r * kRowBytes + ((kc ^ swz(r)) << 4);
+    for (int s = 0; s < CH; ++s) {
+        const int r = 16 * ((wave + NW * s) % BLKS) + (lane >> 2);
+        const int kc = (lane & 3) ^ swz(r);
+        const uint8_t* base = (r < BM) ? qx + (int64_t)min(m0 + r, T - 1) * kb
+                                       : qw + (int64_t)min(n0 + r - BM, N - 1) * kb;
+        src[s] = base + kc * 16;
     }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(PME_AS3 unsigned char*)smem;
+    auto issue = [&](int stage, int kt) {
+#pragma unroll
+        for (int s = 0; s < CH; ++s)
+            dma16(src[s] + (int64_t)kt * kRowBytes,
+                  __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + ((wave + NW * s) % BLKS) * 1024));
+    };
 
     i32x16 acc[FM][FN];
 #pragma unroll
@@ -77,22 +116,8 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
 
-    const int KT = kb / kRowBytes;
-    u32x4 stage_regs[CHUNKS];
-#pragma unroll
-    for (int i = 0; i < CHUNKS; ++i) stage_regs[i] = *reinterpret_cast<const u32x4*>(src[i]);
-#pragma unroll
-    for (int i = 0; i < CHUNKS; ++i) *reinterpret_cast<u32x4*>(smem + dst_off[i]) = stage_regs[i];
-    __syncthreads();
-
     const int frow = lane & 31, fk = lane >> 5;
-    for (int kt = 0; kt < KT; ++kt) {
-        const unsigned char* cur = smem + (kt & 1) * STAGE;
-        if (kt + 1 < KT) {
-#pragma unroll
-            for (int i = 0; i < CHUNKS; ++i)
-                stage_regs[i] = *reinterpret_cast<const u32x4*>(src[i] + (int64_t)(kt + 1) * kRowBytes);
-        }
+    auto compute = [&](const unsigned char* cur) {
 #pragma unroll
         for (int s = 0; s < 2; ++s) {
             i32x4 alo[FM], ahi[FM], blo[FN], bhi[FN];
@@ -101,7 +126,7 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
                 const int r = wm * WM + 32 * i + frow;
                 u32x4 w = *reinterpret_cast<const u32x4*>(cur + r * kRowBytes + (((2 * s + fk) ^ swz(r)) << 4));
                 // unsigned codes u: u ^ 8 read as a signed nibble is u - 8; the epilogue adds 8 * wsum back
-                if (ASYM) w ^= 0x88888888u;
+                if (MODE == MODE_ASYM) w ^= 0x88888888u;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     alo[i][e] = (int)((w[e] & 0x0F0F0F0Fu) << 4);
@@ -122,78 +147,171 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             for (int i = 0; i < FM; ++i)
 #pragma unroll
                 for (int j = 0; j < FN; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(alo[i], blo[j], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(ahi[i], bhi[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(blo[j], alo[i], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bhi[j], ahi[i], acc[i][j], 0, 0, 0);
                 }
         }
-        if (kt + 1 < KT) {
-            unsigned char* nxt = smem + ((kt + 1) & 1) * STAGE;
-#pragma unroll
-            for (int i = 0; i < CHUNKS; ++i) *reinterpret_cast<u32x4*>(nxt + dst_off[i]) = stage_regs[i];
-        }
-        __syncthreads();
+    };
+
+    const int KT = kb / kRowBytes;
+    issue(0, 0);
+    if (KT > 1) {
+        issue(1, 1);
+        wait_vm<CH>();
+    } else {
+        wait_vm<0>();
+    }
+    lds_barrier();
+
+    // One K step: start the DMA two steps ahead (into the stage consumed in the previous step, which
+    // every wave has left), consume the current stage, then wait until the next stage has landed for
+    // every wave.
+    int cur = 0;
+    for (int kt = 0; kt < KT; ++kt) {
+        const bool more = kt + 2 < KT;
+        if (more) issue(cur == 0 ? 2 : cur - 1, kt + 2);
+        compute(smem + cur * STAGE);
+        if (more) wait_vm<CH>(); else wait_vm<0>();
+        lds_barrier();
+        cur = (cur == 2) ? 0 : cur + 1;
     }
 
-    // Epilogue.  Accumulator element e of a 32x32 block: row 8 (e / 4) + 4 (lane / 32) + e % 4, column lane % 32.
-#pragma unroll
-    for (int j = 0; j < FN; ++j) {
-        const int n = n0 + wn * WN + 32 * j + frow;
-        if (n >= N) continue;
-        float swn = 0.f;
-        int ws = 0;
-        if (!OUT_I32) swn = sw[n];
-        if (ASYM) ws = wsum[n];
+    // ---- epilogue.  Accumulator element e of block (i, j): output channel
+    // n0 + wn WN + 32 j + 8 (e / 4) + 4 fk + e % 4, token m0 + wm WM + 32 i + frow.
+    if constexpr (MODE == MODE_I32) {
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
+            const int t = m0 + wm * WM + 32 * i + frow;
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int t = m0 + wm * WM + 32 * i + 8 * (e >> 2) + 4 * fk + (e & 3);
-                if (t >= T) continue;
-                int a = acc[i][j][e] >> 8;      // exact: the low 8 bits are zero
-                if (ASYM) a -= (zx[t] - 8) * ws;
-                if (OUT_I32) {
-                    static_cast<int32_t*>(out)[(int64_t)t * ldo + n] = a;
-                } else {
-                    const float y = (float)a * sx[t] * swn;
-                    static_cast<uint16_t*>(out)[(int64_t)t * ldo + n] = f32_to_bf16_bits(y);
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) {
+                    const int n = n0 + wn * WN + 32 * j + 8 * (e >> 2) + 4 * fk + (e & 3);
+                    if (t < T && n < N) static_cast<int32_t*>(out)[(int64_t)t * ldo + n] = acc[i][j][e] >> 8;
+                }
+        }
+    } else {
+        // all waves are past the last barrier of the K loop: the stages are free for staging
+        unsigned char* slab = smem + (size_t)wave * SLAB;
+        f32x4 swv[FN][4];
+        int wsv[FN][4][4];
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int eg = 0; eg < 4; ++eg)
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int n = min(n0 + wn * WN + 32 * j + 8 * eg + 4 * fk + q, N - 1);
+                    swv[j][eg][q] = sw[n];
+                    if (MODE == MODE_ASYM) wsv[j][eg][q] = wsum[n];
+                }
+        uint16_t* y = static_cast<uint16_t*>(out);
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const int t = min(m0 + wm * WM + 32 * i + frow, T - 1);
+            const float sxs = sx[t] * (1.f / 256.f);          // exact: removes the 16 x 16 of the nibble trick
+            int zoff = 0;
+            if (MODE == MODE_ASYM) zoff = (zx[t] - 8) * 256;
+#pragma unroll
+            for (int j = 0; j < FN; ++j)
+#pragma unroll
+                for (int eg = 0; eg < 4; ++eg) {
+                    float f[4];
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        int a = acc[i][j][4 * eg + q];
+                        if (MODE == MODE_ASYM) a -= zoff * wsv[j][eg][q];
+                        f[q] = (float)a * sxs * swv[j][eg][q];
+                    }
+                    const u32x2 pk = u32x2{pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3])};
+                    *reinterpret_cast<u32x2*>(slab + frow * (WN * 2) + (32 * j + 8 * eg + 4 * fk) * 2) = pk;
+                }
+            // the slab is private to the wave: no workgroup barrier, only this wave's LDS traffic
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            const int tbase = m0 + wm * WM + 32 * i, nbase = n0 + wn * WN;
+            if (vec_store) {
+                constexpr int CPR = WN / 8;                   // 16-byte chunks per slab row
+#pragma unroll
+                for (int c = lane; c < 32 * CPR; c += 64) {
+                    const int row = c / CPR, col = (c % CPR) * 8;
+                    const u32x4 v = *reinterpret_cast<const u32x4*>(slab + row * (WN * 2) + col * 2);
+                    if (tbase + row < T && nbase + col < N)
+                        *reinterpret_cast<u32x4*>(y + (int64_t)(tbase + row) * ldo + nbase + col) = v;
+                }
+            } else {
+                for (int c = lane; c < 32 * WN; c += 64) {
+                    const int row = c / WN, col = c % WN;
+                    if (tbase + row < T && nbase + col < N)
+                        y[(int64_t)(tbase + row) * ldo + nbase + col] =
+                            *reinterpret_cast<const uint16_t*>(slab + row * (WN * 2) + col * 2);
                 }
             }
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
     }
 }
 
-template <int BM, int BN, int WM, int WN>
+template <int BM, int BN, int WGM, int WGN>
 pme_status launch_tile(const GemmArgs& a) {
     const int tiles_m = (int)((a.T + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     const int kb = (int)(a.d_e / 2);
-    const size_t lds = 2 * (size_t)(BM + BN) * kRowBytes;
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(kThreads);
-#define PME_LAUNCH(I32, AS)                                                                              \
-    hipLaunchKernelGGL((k_gemm_mfma<BM, BN, WM, WN, I32, AS>), grid, block, lds, a.stream, a.qx, a.qw, a.sx, \
-                       a.sw, a.zx, a.wsum, (int)a.T, (int)a.N, kb, a.y, a.ldy, tiles_m, tiles_n)
-    if (a.out_i32) PME_LAUNCH(true, false);
-    else if (a.zx) PME_LAUNCH(false, true);
-    else PME_LAUNCH(false, false);
+    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WGM * WGN);
+    const size_t lds = 3 * (size_t)(BM + BN) * kRowBytes;
+    if (lds > 64 * 1024) {
+        // one attribute call per instantiation and mode is enough, but the call is cheap and idempotent
+        hipError_t e0 = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WGM, WGN, MODE_BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e1 = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WGM, WGN, MODE_ASYM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e2 = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WGM, WGN, MODE_I32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e0 != hipSuccess || e1 != hipSuccess || e2 != hipSuccess) return PME_ERR_HIP;
+    }
+    // 16-byte output pieces need 8-element alignment of N, the pitch and the base
+    const int vec = (a.N % 8 == 0 && a.ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0) ? 1 : 0;
+#define PME_LAUNCH(MODE)                                                                                      \
+    hipLaunchKernelGGL((k_gemm_mfma<BM, BN, WGM, WGN, MODE>), grid, block, lds, a.stream, a.qx, a.qw, a.sx, a.sw, \
+                       a.zx, a.wsum, (int)a.T, (int)a.N, kb, a.y, a.ldy, tiles_m, tiles_n, vec)
+    if (a.out_i32) PME_LAUNCH(MODE_I32);
+    else if (a.zx) PME_LAUNCH(MODE_ASYM);
+    else PME_LAUNCH(MODE_BF16);
 #undef PME_LAUNCH
     return hip_status(hipGetLastError());
 }
 
+int g_tile_override = 0;
+
 }  // namespace
+
+void set_gemm_tile_override(int id) { g_tile_override = id; }
 
 pme_status launch_gemm_mfma(const GemmArgs& a) {
     // d_e a multiple of 128 (whole K steps), 16-byte aligned rows, and the x256 accumulator in range.
     if (a.d_e % 128 || a.d_e > (1 << 17)) return PME_ERR_UNSUPPORTED_PATH;
     if ((reinterpret_cast<uintptr_t>(a.qx) & 15) || (reinterpret_cast<uintptr_t>(a.qw) & 15)) return PME_ERR_UNSUPPORTED_PATH;
     if (a.zx && a.out_i32) return PME_ERR_UNSUPPORTED_PATH;
-    // Tile choice: the largest tile that still gives every one of the 256 compute units a workgroup.
     const int64_t cus = 256;
     auto tiles = [&](int bm, int bn) { return ((a.T + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
-    if (tiles(256, 256) >= cus) return launch_tile<256, 256, 128, 128>(a);
-    if (tiles(128, 256) >= cus) return launch_tile<128, 256, 64, 128>(a);
-    if (tiles(128, 192) >= cus) return launch_tile<128, 192, 64, 96>(a);
-    if (tiles(128, 128) >= cus) return launch_tile<128, 128, 64, 64>(a);
-    if (tiles(64, 128) >= cus / 2) return launch_tile<64, 128, 32, 64>(a);
-    return launch_tile<64, 64, 32, 32>(a);
+    int id = g_tile_override;
+    if (id == 0) {
+        // the largest tile that still gives every one of the 256 compute units a workgroup
+        if (tiles(256, 256) >= cus) id = 1;
+        else if (tiles(128, 256) >= cus) id = 2;
+        else if (tiles(128, 192) >= cus) id = 3;
+        else if (tiles(128, 128) >= cus) id = 4;
+        else if (tiles(64, 128) >= cus / 2) id = 6;
+        else id = 7;
+    }
+    switch (id) {
+        case 1: return launch_tile<256, 256, 2, 4>(a);     // 8 waves of 128 x 64
+        case 2: return launch_tile<128, 256, 2, 4>(a);     // 8 waves of 64 x 64
+        case 3: return launch_tile<128, 192, 4, 2>(a);     // 8 waves of 32 x 96
+        case 4: return launch_tile<128, 128, 2, 4>(a);     // 8 waves of 64 x 32
+        case 5: return launch_tile<128, 128, 2, 2>(a);     // 4 waves of 64 x 64
+        case 6: return launch_tile<64, 128, 2, 2>(a);      // 4 waves of 32 x 64
+        case 7: return launch_tile<64, 64, 2, 2>(a);       // 4 waves of 32 x 32
+        case 8: return launch_tile<256, 256, 2, 2>(a);     // 4 waves of 128 x 128
+        case 9: return launch_tile<128, 192, 2, 2>(a);     // 4 waves of 64 x 96
+        case 10: return launch_tile<256, 128, 4, 2>(a);    // 8 waves of 64 x 64
+    }
+    return PME_ERR_UNSUPPORTED_PATH;
 }
 
 }  // namespace pme

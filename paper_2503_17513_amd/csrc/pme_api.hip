@@ -222,6 +222,7 @@ pme_status pme_probe_copy(const void* src, void* dst, size_t bytes, void* stream
     return pme::launch_probe_copy(src, dst, bytes, (hipStream_t)stream);
 }
 
+void pme_set_gemm_tile(int id) { pme::set_gemm_tile_override(id); }
 void pme_set_path(pme_path p) { g_path.store((int)p); }
 pme_path pme_get_path(void) { return (pme_path)g_path.load(); }
 

@@ -18,6 +18,8 @@
 // Waves split the token by a' (16-wide tiles, TPW tiles per wave); the FWHT never crosses a'.
 #include "pme_internal.h"
 
+#include <mutex>
+
 namespace pme {
 namespace {
 
@@ -134,63 +136,128 @@ __device__ __forceinline__ uint32_t split_hi(float f, float& rem) {
     return hi >> 16;
 }
 
-template <int KLOG2, int KS, int TPW, bool F32IN>
+// ---------------------------------------------------------------------------------------------
+// B-operand table: the Paley block as ready-made bf16 MFMA fragments, built once per
+// (device, b, real base rows) by a small kernel and kept in device memory owned by the library.
+// Entry (tile, ks), lane (a' = 16 tile + lane % 16, g = lane / 16) holds P[32 ks + 8 g + e][a'],
+// e = 0..7 (+-1 in bf16; 0 outside the block or beyond the rows that hold real inputs).
+// ---------------------------------------------------------------------------------------------
+constexpr int kMaxTiles = 10, kMaxKs = 5, kSlots = 8;
+__device__ __align__(256) u32x4 g_ptable[kSlots][kMaxTiles * kMaxKs][64];
+
+__global__ void __launch_bounds__(64) k_fill_ptable(int slot, int b, int rows) {
+    __shared__ signed char chi[256];
+    const int lane = threadIdx.x, q = b - 1;
+    if (b > 1) {
+        for (int i = lane; i < q; i += 64) chi[i] = (i == 0) ? 0 : -1;
+        __syncthreads();
+        for (int i = 1 + lane; i < q; i += 64) chi[(i * i) % q] = 1;
+        __syncthreads();
+    }
+    const int tile = blockIdx.x / kMaxKs, ks = blockIdx.x % kMaxKs;
+    const int ap = tile * 16 + (lane & 15), g = lane >> 4;
+    u32x4 pk;
+#pragma unroll
+    for (int p = 0; p < 4; ++p) {
+        uint32_t word = 0;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int a = 32 * ks + 8 * g + 2 * p + h;
+            uint32_t bits = 0;
+            if (a < rows && a < b && ap < b) {
+                const int sgn = (b > 1) ? paley_entry(chi, q, a, ap) : 1;
+                bits = sgn > 0 ? 0x3F80u : 0xBF80u;
+            }
+            word |= bits << (16 * h);
+        }
+        pk[p] = word;
+    }
+    g_ptable[slot][blockIdx.x][lane] = pk;
+}
+
+struct TableKey { int device, b, rows; };
+std::mutex g_table_mutex;
+TableKey g_table_keys[kSlots];
+int g_table_used = 0, g_table_next = 0;
+
+// Returns the slot holding the table for (b, rows) on the current device, building it on a miss.
+// A miss launches the fill kernel on `stream` and waits for it once, so that callers on other
+// streams never see a half-written table.  With more than kSlots live shapes per process the
+// oldest slot is reused; calls still in flight on that shape would then race with the refill.
+int table_slot(int b, int rows, hipStream_t stream, pme_status* st) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) { *st = PME_ERR_HIP; return -1; }
+    std::lock_guard<std::mutex> lock(g_table_mutex);
+    for (int i = 0; i < g_table_used; ++i)
+        if (g_table_keys[i].device == dev && g_table_keys[i].b == b && g_table_keys[i].rows == rows) return i;
+    const int slot = g_table_next;
+    hipLaunchKernelGGL(k_fill_ptable, dim3(kMaxTiles * kMaxKs), dim3(64), 0, stream, slot, b, rows);
+    if (hipGetLastError() != hipSuccess || hipStreamSynchronize(stream) != hipSuccess) { *st = PME_ERR_HIP; return -1; }
+    g_table_keys[slot] = TableKey{dev, b, rows};
+    g_table_next = (g_table_next + 1) % kSlots;
+    if (g_table_used < kSlots) ++g_table_used;
+    return slot;
+}
+
+#define PME_AS1 __attribute__((address_space(1)))
+#define PME_AS3 __attribute__((address_space(3)))
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+
+// Physical LDS position (in 16-byte chunks) of the 8 inputs (a, c .. c+7), c a multiple of 8, in the
+// bf16 layout: blocks of 4 rows x 16 columns stored contiguously (128 bytes), so that the 16 lanes of
+// a transposing LDS read touch one contiguous 128-byte block.
+template <int MT> __device__ __forceinline__ int chunk_of(int a, int c) {
+    return ((a >> 2) * MT + (c >> 4)) * 8 + (a & 3) * 2 + ((c >> 3) & 1);
+}
+
+template <int KLOG2, int TPW, bool F32IN>
 __global__ void __launch_bounds__(64 * kMaxWaves)
-k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int d, int d_e, int b, double gamma,
-              uint8_t* __restrict__ qx, float* __restrict__ sx, int32_t* __restrict__ zx,
+k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int d, int d_e, int b, int ks_count, int slot,
+              double gamma, uint8_t* __restrict__ qx, float* __restrict__ sx, int32_t* __restrict__ zx,
               float* __restrict__ xhat) {
     using L = Layout<KLOG2>;
     constexpr int NC = L::NC, MT = L::MT, NREG = L::NREG;
     constexpr int NS = F32IN ? 3 : 1;
-    constexpr int FRAG_BYTES = KS * MT * 64 * 16;    // one bf16 copy of the token in fragment order
+    const int plane_bytes = ks_count * MT * 1024;     // one bf16 copy of the K-padded token
 
-    extern __shared__ __align__(16) unsigned char smem[];
-    unsigned char* afrag = smem;                                        // NS * FRAG_BYTES
-    float* red = reinterpret_cast<float*>(smem + NS * FRAG_BYTES);     // 2 * kMaxWaves floats
-    signed char* chi = reinterpret_cast<signed char*>(red + 2 * kMaxWaves);
+    extern __shared__ __align__(16) unsigned char smem[];   // NS * plane_bytes
+    __shared__ float red[2 * kMaxWaves];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nwaves = blockDim.x >> 6;
+    const int nwaves = blockDim.x >> 6, nthreads = blockDim.x;
     const int64_t t = blockIdx.x;
-    const int q = b - 1;
-    const int rows = (d + NC - 1) >> KLOG2;          // base rows with real inputs (<= 32 * KS)
     const int l15 = lane & 15, g = lane >> 4;
+    const int rows_k = 32 * ks_count;                 // rows of the K-padded operand
 
-    if (b > 1) {
-        for (int i = tid; i < q; i += blockDim.x) chi[i] = (i == 0) ? 0 : -1;
-        __syncthreads();
-        for (int i = 1 + tid; i < q; i += blockDim.x) chi[(i * i) % q] = 1;
-    }
-
-    // ---- 1. token -> LDS, in A-fragment order: fragment (ks, mt), slot (c % 16) + 16 g holds
-    //         the 8 values a = 32 ks + 8 g + e (e = 0..7) of column c = 16 mt + c % 16.
     if constexpr (!F32IN) {
-        const uint16_t* xr = static_cast<const uint16_t*>(xv) + t * ldx;
-        constexpr int UNITS = KS * 4 * (NC / 2);
-        for (int u = tid; u < UNITS; u += blockDim.x) {
-            const int cp = u % (NC / 2), ag = u / (NC / 2);
-            const int c = 2 * cp, a0 = 8 * ag;
-            uint32_t w[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const int i = (a0 + e) * NC + c;
-                w[e] = (i < d) ? *reinterpret_cast<const uint32_t*>(xr + i) : 0u;
-            }
-            u32x4 ev, od;
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                ev[p] = (w[2 * p] & 0xFFFFu) | (w[2 * p + 1] << 16);
-                od[p] = (w[2 * p] >> 16) | (w[2 * p + 1] & 0xFFFF0000u);
-            }
-            const int ks = ag >> 2, gg = ag & 3, mt = c >> 4;
-            unsigned char* dst = afrag + ((size_t)((ks * MT + mt) * 64 + (c & 15) + 16 * gg)) * 16;
-            *reinterpret_cast<u32x4*>(dst) = ev;
-            *reinterpret_cast<u32x4*>(dst + 16) = od;
+        // ---- 1a. bf16 token: HBM -> LDS by DMA, 16 bytes per lane, laid out for transposing reads.
+        const unsigned char* xr = reinterpret_cast<const unsigned char*>(static_cast<const uint16_t*>(xv) + t * ldx);
+        const int real_groups = (((d + NC - 1) >> KLOG2) + 3) >> 2;        // 4-row groups holding real inputs
+        const int nchunks = real_groups * MT * 8;
+        for (int base = wave * 64; base < nchunks; base += nwaves * 64) {
+            const int p = base + lane;
+            const int blk = p >> 3, r = p & 7;
+            const int a = 4 * (blk / MT) + (r >> 1), c = 16 * (blk % MT) + 8 * (r & 1);
+            const int i = a * NC + c;
+            if (p < nchunks && i < d)
+                __builtin_amdgcn_global_load_lds((const PME_AS1 void*)(xr + 2 * (size_t)i),
+                                                 (PME_AS3 void*)(smem + (size_t)base * 16), 16, 0, 0);
+        }
+        // chunks of the K-padded operand that hold no input are zero
+        const int first = ((d >> KLOG2) >> 2) * MT * 8;
+        const int total = (rows_k >> 2) * MT * 8;
+        for (int p = first + tid; p < total; p += nthreads) {
+            const int blk = p >> 3, r = p & 7;
+            const int a = 4 * (blk / MT) + (r >> 1), c = 16 * (blk % MT) + 8 * (r & 1);
+            if (a * NC + c >= d) *reinterpret_cast<u32x4*>(smem + (size_t)p * 16) = u32x4{0u, 0u, 0u, 0u};
         }
     } else {
+        // ---- 1b. fp32 token: split every input into three bf16 terms (exact sum) and store each term
+        //          plane in A-fragment order: fragment (ks, mt), slot (c % 16) + 16 g holds the 8 values
+        //          a = 32 ks + 8 g + e of column c = 16 mt + c % 16.
         const float* xr = static_cast<const float*>(xv) + t * ldx;
-        constexpr int UNITS = KS * 4 * NC;
-        for (int u = tid; u < UNITS; u += blockDim.x) {
+        const int units = ks_count * 4 * NC;
+        for (int u = tid; u < units; u += nthreads) {
             const int c = u % NC, ag = u / NC;
             const int a0 = 8 * ag;
             uint32_t h0[8], h1[8], h2[8];
@@ -204,7 +271,7 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int d, int d_e, int b, d
                 h2[e] = split_hi(r2, r3);
             }
             const int ks = ag >> 2, gg = ag & 3, mt = c >> 4;
-            unsigned char* dst = afrag + ((size_t)((ks * MT + mt) * 64 + (c & 15) + 16 * gg)) * 16;
+            unsigned char* dst = smem + ((size_t)((ks * MT + mt) * 64 + (c & 15) + 16 * gg)) * 16;
             u32x4 p0, p1, p2;
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
@@ -213,62 +280,59 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int d, int d_e, int b, d
                 p2[p] = h2[2 * p] | (h2[2 * p + 1] << 16);
             }
             *reinterpret_cast<u32x4*>(dst) = p0;
-            *reinterpret_cast<u32x4*>(dst + FRAG_BYTES) = p1;
-            *reinterpret_cast<u32x4*>(dst + 2 * FRAG_BYTES) = p2;
+            *reinterpret_cast<u32x4*>(dst + plane_bytes) = p1;
+            *reinterpret_cast<u32x4*>(dst + 2 * plane_bytes) = p2;
         }
     }
+    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): the DMA writes have landed
     __syncthreads();
 
-    // ---- 2. B fragments of P for this wave's a'-tiles: lane (a' = 16 tile + l15, g) holds
-    //         P[32 ks + 8 g + e][a'], e = 0..7, as bf16 (+-1, 0 outside the block or the real rows).
-    bf16x8 bfrag[TPW][KS];
-#pragma unroll
-    for (int ti = 0; ti < TPW; ++ti) {
-        const int ap = (wave * TPW + ti) * 16 + l15;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            u32x4 pk;
-#pragma unroll
-            for (int p = 0; p < 4; ++p) {
-                uint32_t word = 0;
-#pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int a = 32 * ks + 8 * g + 2 * p + h;
-                    uint32_t bits = 0;
-                    if (a < rows && a < b && ap < b) {
-                        const int sgn = (b > 1) ? paley_entry(chi, q, a, ap) : 1;
-                        bits = sgn > 0 ? 0x3F80u : 0xBF80u;
-                    }
-                    word |= bits << (16 * h);
-                }
-                pk[p] = word;
-            }
-            bfrag[ti][ks] = __builtin_bit_cast(bf16x8, pk);
-        }
-    }
-
-    // ---- 3. base block on the matrix cores
+    // ---- 2. base block on the matrix cores: Z^T[c][a'] = sum_a X~[a][c] P[a][a']
     f32x4 acc[TPW][MT];
 #pragma unroll
     for (int ti = 0; ti < TPW; ++ti)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) acc[ti][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    const int ntiles = (b + 15) >> 4;
+    for (int ks = 0; ks < ks_count; ++ks) {
+        bf16x8 bfrag[TPW];
 #pragma unroll
-    for (int mt = 0; mt < MT; ++mt)
+        for (int ti = 0; ti < TPW; ++ti) {
+            const int tile = min(wave * TPW + ti, kMaxTiles - 1);
+            bfrag[ti] = __builtin_bit_cast(bf16x8, g_ptable[slot][tile * kMaxKs + ks][lane]);
+        }
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-            for (int sp = 0; sp < NS; ++sp) {
-                const u32x4 raw = *reinterpret_cast<const u32x4*>(
-                    afrag + (size_t)sp * FRAG_BYTES + ((size_t)((ks * MT + mt) * 64 + lane)) * 16);
-                const bf16x8 af = __builtin_bit_cast(bf16x8, raw);
+        for (int mt = 0; mt < MT; ++mt) {
+            if constexpr (!F32IN) {
+                // two transposing reads: lane (g, j = lane % 16) addresses 8 bytes of row 32 ks + 8 g + 4 h + j / 4
+                // and receives rows 32 ks + 8 g + 4 h + (0..3) of column 16 mt + j.
+                const unsigned char* p0 = smem + ((size_t)((8 * ks + 2 * g) * MT + mt)) * 128 + 8 * l15;
+                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 PME_AS3*)p0);
+                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 PME_AS3*)(p0 + MT * 128));
+                typedef __attribute__((ext_vector_type(8))) short s16x8;
+                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                const bf16x8 af = __builtin_bit_cast(bf16x8, both);
 #pragma unroll
                 for (int ti = 0; ti < TPW; ++ti)
-                    acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfrag[ti][ks], acc[ti][mt], 0, 0, 0);
+                    if ((wave * TPW + ti) < ntiles)
+                        acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfrag[ti], acc[ti][mt], 0, 0, 0);
+            } else {
+#pragma unroll
+                for (int sp = 0; sp < NS; ++sp) {
+                    const u32x4 raw = *reinterpret_cast<const u32x4*>(
+                        smem + (size_t)sp * plane_bytes + ((size_t)((ks * MT + mt) * 64 + lane)) * 16);
+                    const bf16x8 af = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+                    for (int ti = 0; ti < TPW; ++ti)
+                        if ((wave * TPW + ti) < ntiles)
+                            acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfrag[ti], acc[ti][mt], 0, 0, 0);
+                }
             }
+        }
+    }
 
-    // ---- 4. FWHT along c, in registers
+    // ---- 3. FWHT along c, in registers
     float v[TPW][NREG];
 #pragma unroll
     for (int ti = 0; ti < TPW; ++ti) {
@@ -276,7 +340,7 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int d, int d_e, int b, d
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
             for (int r = 0; r < 4; ++r) v[ti][mt * 4 + r] = acc[ti][mt][r];
-        fwht_lane<KLOG2>(v[ti]);
+        if ((wave * TPW + ti) < ntiles) fwht_lane<KLOG2>(v[ti]);
     }
 
     const int l4 = (lane >> 4) & 1, l5 = lane >> 5;
@@ -296,21 +360,24 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int d, int d_e, int b, d
     }
     if (!qx) return;
 
-    // ---- 5. per-token range
+    // ---- 4. per-token range
     float hi = 0.f, lo = 0.f;
+    if (zx) {
 #pragma unroll
-    for (int ti = 0; ti < TPW; ++ti)
+        for (int ti = 0; ti < TPW; ++ti)
 #pragma unroll
-        for (int i = 0; i < NREG; ++i) {
-            if (zx) {
+            for (int i = 0; i < NREG; ++i) {
                 hi = fmaxf(hi, v[ti][i]);
                 lo = fminf(lo, v[ti][i]);
-            } else {
-                hi = fmaxf(hi, fabsf(v[ti][i]));
             }
-        }
+        lo = wave_min(lo);
+    } else {
+#pragma unroll
+        for (int ti = 0; ti < TPW; ++ti)
+#pragma unroll
+            for (int i = 0; i < NREG; i += 2) hi = fmaxf(hi, fmaxf(fabsf(v[ti][i]), fabsf(v[ti][i + 1])));
+    }
     hi = wave_max(hi);
-    if (zx) lo = wave_min(lo);
     if (nwaves > 1) {
         if (lane == 0) { red[wave] = hi; red[kMaxWaves + wave] = lo; }
         __syncthreads();
@@ -338,24 +405,38 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int d, int d_e, int b, d
         if (tid == 0) { sx[t] = s; zx[t] = z; }
     }
 
-    // ---- 6. round, pack, store.  fma(u, rinv, 1.5 * 2^23) leaves rne(u * rinv) in the low
-    //         mantissa bits as a two's-complement integer.
-    const float magic = 12582912.f;
+    // ---- 5. round, pack, store.
+    // fma(u, rinv, 1.5 * 2^23 + 8) has the bit pattern C + e with C = 0x4B400000 and e = rne(u * rinv) + 8
+    // in [1, 15].  Eight of them are combined by Horner steps acc = (acc << 4) + bits; the digits are
+    // non-negative, so no carries cross nibbles, and the accumulated constant C * 0x11111111 is
+    // subtracted once.  e ^ 8 is the 4-bit two's-complement code.
+    constexpr uint32_t kC = 0x4B400000u;
+    constexpr uint32_t kCsum = kC * 0x11111111u;
 #pragma unroll
     for (int ti = 0; ti < TPW; ++ti) {
         const int ap = (wave * TPW + ti) * 16 + l15;
         uint32_t words[L::RUN / 8];
 #pragma unroll
         for (int wd = 0; wd < L::RUN / 8; ++wd) {
-            uint32_t word = 0;
+            if (!zx) {
+                uint32_t accw = 0;
 #pragma unroll
-            for (int nb = 0; nb < 8; ++nb) {
-                const float f = __builtin_fmaf(v[ti][L::reg_of_run_pos(wd * 8 + nb)], rinv, magic);
-                int code = (int)(__float_as_uint(f) & 0x7FFFFFu) - 0x400000;   // exact integer
-                if (zx) code = min(15, max(0, code + z));
-                word |= ((uint32_t)code & 0xFu) << (4 * nb);
+                for (int nb = 7; nb >= 0; --nb) {
+                    const float f = __builtin_fmaf(v[ti][L::reg_of_run_pos(wd * 8 + nb)], rinv, 12582920.f);
+                    accw = (accw << 4) + __float_as_uint(f);
+                }
+                words[wd] = (accw - kCsum) ^ 0x88888888u;
+            } else {
+                uint32_t accw = 0;
+#pragma unroll
+                for (int nb = 7; nb >= 0; --nb) {
+                    const float f = __builtin_fmaf(v[ti][L::reg_of_run_pos(wd * 8 + nb)], rinv, 12582912.f);
+                    int code = (int)(__float_as_uint(f) - kC) + z;
+                    code = min(15, max(0, code));
+                    accw = (accw << 4) + (uint32_t)code;
+                }
+                words[wd] = accw;
             }
-            words[wd] = word;
         }
         if (ap < b) {
             uint8_t* o = qx + t * (int64_t)(d_e / 2) + (((int64_t)ap * NC + c0) >> 1);
@@ -372,48 +453,41 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int d, int d_e, int b, d
     }
 }
 
-template <int KLOG2, int KS, int TPW, bool F32IN>
-pme_status launch_one(const RotateArgs& a, int nwaves) {
+template <int KLOG2, int TPW, bool F32IN>
+pme_status launch_one(const RotateArgs& a, int ks, int nwaves) {
     using L = Layout<KLOG2>;
     constexpr int NS = F32IN ? 3 : 1;
-    const size_t lds = (size_t)NS * KS * L::MT * 64 * 16 + 2 * kMaxWaves * 4 + 256;
-    if (lds > 160 * 1024) return PME_ERR_UNSUPPORTED_PATH;
-    auto kern = k_rotate_mfma<KLOG2, KS, TPW, F32IN>;
-    if (lds > 64 * 1024) {
+    const size_t lds = (size_t)NS * ks * L::MT * 1024;
+    if (lds + 256 > 160 * 1024) return PME_ERR_UNSUPPORTED_PATH;
+    const int rows = (int)((a.d + L::NC - 1) >> KLOG2);
+    pme_status st = PME_OK;
+    const int slot = table_slot(a.b, rows, a.stream, &st);
+    if (slot < 0) return st;
+    auto kern = k_rotate_mfma<KLOG2, TPW, F32IN>;
+    if (lds > 48 * 1024) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return PME_ERR_HIP;
     }
     const double gamma = 1.0 / sqrt((double)a.d_e);
     hipLaunchKernelGGL(kern, dim3((unsigned)a.T), dim3(64 * nwaves), lds, a.stream, a.x, a.ldx, (int)a.d,
-                       (int)a.d_e, a.b, gamma, a.qx, a.sx, a.zx, a.xhat);
+                       (int)a.d_e, a.b, ks, slot, gamma, a.qx, a.sx, a.zx, a.xhat);
     return hip_status(hipGetLastError());
-}
-
-template <int KLOG2, bool F32IN, int TPW>
-pme_status dispatch_ks(const RotateArgs& a, int ks, int nwaves) {
-    switch (ks) {
-        case 1: return launch_one<KLOG2, 1, TPW, F32IN>(a, nwaves);
-        case 2: return launch_one<KLOG2, 2, TPW, F32IN>(a, nwaves);
-        case 3: return launch_one<KLOG2, 3, TPW, F32IN>(a, nwaves);
-        case 4: return launch_one<KLOG2, 4, TPW, F32IN>(a, nwaves);
-        case 5: return launch_one<KLOG2, 5, TPW, F32IN>(a, nwaves);
-    }
-    return PME_ERR_UNSUPPORTED_PATH;
 }
 
 }  // namespace
 
 pme_status launch_rotate_mfma(const RotateArgs& a) {
-    // Shapes covered: 32 <= 2^k <= 512; even d and even row pitch for bf16 input (pairs of inputs
-    // are loaded as dwords); 16-byte aligned code rows.
+    // Shapes covered: 32 <= 2^k <= 512.  bf16 input is copied to LDS in 16-byte pieces, so d, the row
+    // pitch and the base address must be multiples of 8 elements; code rows must be 16-byte aligned.
     if (a.k < 5 || a.k > 9) return PME_ERR_UNSUPPORTED_PATH;
     const bool f32 = a.xt == PME_F32;
-    if (!f32 && ((a.d & 1) || (a.ldx & 1) || (reinterpret_cast<uintptr_t>(a.x) & 3))) return PME_ERR_UNSUPPORTED_PATH;
+    if (!f32 && ((a.d & 7) || (a.ldx & 7) || (reinterpret_cast<uintptr_t>(a.x) & 15))) return PME_ERR_UNSUPPORTED_PATH;
     if (a.qx && (reinterpret_cast<uintptr_t>(a.qx) & 15)) return PME_ERR_UNSUPPORTED_PATH;
     const int nc = 1 << a.k;
     const int rows = (int)((a.d + nc - 1) >> a.k);
     const int ks = (rows + 31) / 32;
     const int nt = (a.b + 15) / 16;
+    if (ks > kMaxKs || nt > kMaxTiles) return PME_ERR_UNSUPPORTED_PATH;
     // a'-tiles per wave: bounded by registers (4 * 2^k / 16 accumulators per tile).
     int tpw;
     switch (a.k) {
@@ -429,7 +503,7 @@ pme_status launch_rotate_mfma(const RotateArgs& a) {
     if (nwaves > kMaxWaves) return PME_ERR_UNSUPPORTED_PATH;
 #define PME_ROT(K, TP)                                                             \
     if (a.k == K && tpw == TP)                                                     \
-        return f32 ? dispatch_ks<K, true, TP>(a, ks, nwaves) : dispatch_ks<K, false, TP>(a, ks, nwaves);
+        return f32 ? launch_one<K, TP, true>(a, ks, nwaves) : launch_one<K, TP, false>(a, ks, nwaves);
     PME_ROT(5, 5) PME_ROT(5, 1)
     PME_ROT(6, 3) PME_ROT(6, 1)
     PME_ROT(7, 3) PME_ROT(7, 1)

@@ -32,16 +32,17 @@ ROTATE_CASES = [
     ("b68_k7_many_tokens", 600, 8192, 8704, "bf16", (MFMA,)),
     ("b60_k8_many_tokens", 520, 14336, 15360, "bf16", (MFMA,)),
     ("ragged_d_inside_base_row", 6, 2000, 2176, "bf16", (GENERIC, MFMA)),
-    ("ragged_d_small", 6, 300, 2176, "bf16", (GENERIC, MFMA)),
+    ("ragged_d_small", 6, 304, 2176, "bf16", (GENERIC, MFMA)),
+    ("ragged_d_not_multiple_of_8", 6, 300, 2176, "bf16", (GENERIC,)),
     ("odd_d", 4, 301, 2176, "bf16", (GENERIC,)),
     ("f32_b68_k5", 7, 2048, 2176, "f32", (GENERIC, MFMA)),
     ("f32_b132_k6", 3, 8192, 8448, "f32", (GENERIC, MFMA)),
     ("pow2_ratio_one", 5, 256, 256, "bf16", (GENERIC, MFMA)),
     ("pow2_padded", 5, 200, 256, "f32", (GENERIC, MFMA)),
     ("pow2_k12", 3, 4096, 4096, "bf16", (GENERIC,)),
-    ("b12_k6", 4, 700, 768, "bf16", (GENERIC, MFMA)),
+    ("b12_k6", 4, 696, 768, "bf16", (GENERIC, MFMA)),
     ("b20_k5", 4, 600, 640, "bf16", (GENERIC, MFMA)),
-    ("b72_k5", 4, 2100, 2304, "bf16", (GENERIC, MFMA)),
+    ("b72_k5", 4, 2104, 2304, "bf16", (GENERIC, MFMA)),
     ("b140_k6", 3, 8192, 8960, "bf16", (GENERIC, MFMA)),
     ("b152_k6", 3, 8192, 9728, "bf16", (GENERIC, MFMA)),
     ("b20_k9", 3, 8192, 10240, "bf16", (GENERIC, MFMA)),
