@@ -36,14 +36,14 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 #define PME_AS1 __attribute__((address_space(1)))
 #define PME_AS3 __attribute__((address_space(3)))
 
-constexpr int kRowBytes = 64;     // packed bytes per tile row per K step (128 codes)
 enum { MODE_BF16 = 0, MODE_ASYM = 1, MODE_I32 = 2 };
 
-// LDS swizzle: the 16-byte chunk kc (0..3) of tile row r sits at chunk position kc ^ swz(r), so that
-// the rows read together by one ds_read_b128 spread over the banks.
-__device__ __forceinline__ int swz(int r) { return ((r >> 1) ^ (r >> 3)) & 3; }
+// LDS swizzle: the 16-byte chunk kc of tile row r sits at chunk position kc ^ swz(r), so that the rows
+// read together by one ds_read_b128 spread over the banks.  RB = bytes per tile row per K step.
+template <int RB> __device__ __forceinline__ int swz(int r) {
+    return RB == 64 ? (((r >> 1) ^ (r >> 3)) & 3) : ((r >> 1) & 7);
+}
 
-// LDS-only barrier: DMA (vmcnt) stays in flight across it.
 // LDS-only barrier: DMA (counted by vmcnt) stays in flight across it.
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
@@ -59,24 +59,29 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     return __builtin_bit_cast(uint32_t, p);
 }
 
-template <int BM, int BN, int WGM, int WGN, int MODE>
+// BM x BN output tile, WGM x WGN waves, RB packed bytes (2 RB codes) per row and K step, NSTAGE LDS stages.
+template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE, int MODE>
 __global__ void __launch_bounds__(64 * WGM * WGN)
 k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             const float* __restrict__ sx, const float* __restrict__ sw,
             const int32_t* __restrict__ zx, const int32_t* __restrict__ wsum,
             int T, int N, int kb, void* __restrict__ out, int64_t ldo, int tiles_m, int tiles_n, int vec_store) {
-    constexpr int NW = WGM * WGN, NT = 64 * NW;
+    constexpr int NW = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
     constexpr int ROWS = BM + BN;
-    constexpr int BLKS = ROWS / 16;               // 1 KB DMA blocks (16 rows) per stage
+    constexpr int CPR = RB / 16;                  // 16-byte chunks per row
+    constexpr int RPB = 64 / CPR;                 // rows per 1 KB DMA block
+    constexpr int BLKS = ROWS / RPB;              // DMA blocks per stage
     // DMA instructions per wave per stage.  Every wave issues the same number (the per-step wait counts
     // on it); when the blocks do not divide evenly the surplus instructions repeat an earlier block.
     constexpr int CH = (BLKS + NW - 1) / NW;
-    constexpr int STAGE = ROWS * kRowBytes;
+    constexpr int STAGE = ROWS * RB;
+    constexpr int NSUB = RB / 32;                 // sub-steps of 64 codes per K step
     constexpr int SLAB = 32 * WN * 2;             // epilogue: one 32-token slab of the wave tile in bf16
-    static_assert(NW * SLAB <= 3 * STAGE, "epilogue staging must fit in the K-loop stages");
+    static_assert(NW * SLAB <= NSTAGE * STAGE, "epilogue staging must fit in the K-loop stages");
+    static_assert(NSTAGE == 2 || NSTAGE == 3, "two or three stages");
 
-    extern __shared__ __align__(1024) unsigned char smem[];      // 3 stages
+    extern __shared__ __align__(1024) unsigned char smem[];      // NSTAGE stages
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
@@ -89,13 +94,13 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     const int tm = tile / tiles_n, tn = tile % tiles_n;
     const int m0 = tm * BM, n0 = tn * BN;
 
-    // DMA source of each 16-byte chunk this lane moves: block blk = wave + NW s covers tile rows
-    // 16 blk .. 16 blk + 15; lane L writes chunk position L % 4 of row 16 blk + L / 4.
+    // DMA source of each 16-byte chunk this lane moves: block blk covers tile rows RPB blk .. RPB blk + RPB - 1;
+    // lane L writes chunk position L % CPR of row RPB blk + L / CPR, which holds chunk (L % CPR) ^ swz(row).
     const uint8_t* src[CH];
 #pragma unroll
     for (int s = 0; s < CH; ++s) {
-        const int r = 16 * ((wave + NW * s) % BLKS) + (lane >> 2);
-        const int kc = (lane & 3) ^ swz(r);
+        const int r = RPB * ((wave + NW * s) % BLKS) + lane / CPR;
+        const int kc = (lane % CPR) ^ swz<RB>(r);
         const uint8_t* base = (r < BM) ? qx + (int64_t)min(m0 + r, T - 1) * kb
                                        : qw + (int64_t)min(n0 + r - BM, N - 1) * kb;
         src[s] = base + kc * 16;
@@ -104,7 +109,7 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     auto issue = [&](int stage, int kt) {
 #pragma unroll
         for (int s = 0; s < CH; ++s)
-            dma16(src[s] + (int64_t)kt * kRowBytes,
+            dma16(src[s] + (int64_t)kt * RB,
                   __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + ((wave + NW * s) % BLKS) * 1024));
     };
 
@@ -117,64 +122,120 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
 
     const int frow = lane & 31, fk = lane >> 5;
-    auto compute = [&](const unsigned char* cur) {
+    // LDS byte offsets of this lane's fragments within a stage for sub-step 0; sub-step s reads logical
+    // chunk 2 s + fk, i.e. position (2 s + fk) ^ swz(r) = (fk ^ swz(r)) ^ 2 s.
+    int aoff[FM], boff[FN];
 #pragma unroll
-        for (int s = 0; s < 2; ++s) {
-            i32x4 alo[FM], ahi[FM], blo[FN], bhi[FN];
+    for (int i = 0; i < FM; ++i) {
+        const int r = wm * WM + 32 * i + frow;
+        aoff[i] = r * RB + ((fk ^ swz<RB>(r)) << 4);
+    }
 #pragma unroll
-            for (int i = 0; i < FM; ++i) {
-                const int r = wm * WM + 32 * i + frow;
-                u32x4 w = *reinterpret_cast<const u32x4*>(cur + r * kRowBytes + (((2 * s + fk) ^ swz(r)) << 4));
-                // unsigned codes u: u ^ 8 read as a signed nibble is u - 8; the epilogue adds 8 * wsum back
-                if (MODE == MODE_ASYM) w ^= 0x88888888u;
+    for (int j = 0; j < FN; ++j) {
+        const int r = BM + wn * WN + 32 * j + frow;
+        boff[j] = r * RB + ((fk ^ swz<RB>(r)) << 4);
+    }
+    struct Frags { u32x4 a[FM], b[FN]; };                         // 32 packed codes per lane and fragment
+    struct Unpacked { i32x4 alo[FM], ahi[FM], blo[FN], bhi[FN]; };   // the same as int8 x 16 MFMA operands
+    auto load_frags = [&](Frags& f, const unsigned char* stage, int s) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    alo[i][e] = (int)((w[e] & 0x0F0F0F0Fu) << 4);
-                    ahi[i][e] = (int)(w[e] & 0xF0F0F0F0u);
-                }
+        for (int i = 0; i < FM; ++i) f.a[i] = *reinterpret_cast<const u32x4*>(stage + (aoff[i] ^ (s << 5)));
+#pragma unroll
+        for (int j = 0; j < FN; ++j) f.b[j] = *reinterpret_cast<const u32x4*>(stage + (boff[j] ^ (s << 5)));
+    };
+    auto unpack = [&](const Frags& f, Unpacked& u) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            u32x4 w = f.a[i];
+            // unsigned codes c: c ^ 8 read as a signed nibble is c - 8; the epilogue adds 8 * wsum back
+            if (MODE == MODE_ASYM) w ^= 0x88888888u;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                u.alo[i][e] = (int)((w[e] & 0x0F0F0F0Fu) << 4);
+                u.ahi[i][e] = (int)(w[e] & 0xF0F0F0F0u);
             }
+        }
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                u.blo[j][e] = (int)((f.b[j][e] & 0x0F0F0F0Fu) << 4);
+                u.bhi[j][e] = (int)(f.b[j][e] & 0xF0F0F0F0u);
+            }
+    };
+    auto mfma_all = [&](const Unpacked& u) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
             for (int j = 0; j < FN; ++j) {
-                const int r = BM + wn * WN + 32 * j + frow;
-                const u32x4 w = *reinterpret_cast<const u32x4*>(cur + r * kRowBytes + (((2 * s + fk) ^ swz(r)) << 4));
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    blo[j][e] = (int)((w[e] & 0x0F0F0F0Fu) << 4);
-                    bhi[j][e] = (int)(w[e] & 0xF0F0F0F0u);
-                }
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.blo[j], u.alo[i], acc[i][j], 0, 0, 0);
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.bhi[j], u.ahi[i], acc[i][j], 0, 0, 0);
             }
+    };
+    // Scheduling request for one sub-step region (the LDS reads of sub-step g + 2, the unpack arithmetic
+    // of g + 1, the matrix instructions of g): reads first, then the unpack instructions spread evenly
+    // behind the matrix instructions, where a single wave issues them while the matrix pipe is busy.
+    constexpr int NMFMA = 2 * FM * FN;
+    constexpr int NVALU = (FM + FN) * 12 + (MODE == MODE_ASYM ? FM * 4 : 0);
+    constexpr int VPM = (NVALU + NMFMA - 1) / NMFMA;
+    auto interleave = [&](bool with_reads) {
+        if (with_reads) __builtin_amdgcn_sched_group_barrier(0x100, FM + FN, 0);
 #pragma unroll
-            for (int i = 0; i < FM; ++i)
-#pragma unroll
-                for (int j = 0; j < FN; ++j) {
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(blo[j], alo[i], acc[i][j], 0, 0, 0);
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(bhi[j], ahi[i], acc[i][j], 0, 0, 0);
-                }
+        for (int m = 0; m < NMFMA; ++m) {
+            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+            __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
         }
     };
 
-    const int KT = kb / kRowBytes;
-    issue(0, 0);
-    if (KT > 1) {
-        issue(1, 1);
-        wait_vm<CH>();
-    } else {
-        wait_vm<0>();
-    }
+    // Software pipeline over sub-steps g = kt NSUB + s (K step kt lives in stage kt % NSTAGE):
+    //   region g:  read the fragments of g + 2 | unpack those of g + 1 | matrix cores on g.
+    // Before the region whose read first touches K step kt + 1 (s = NSUB - 2) every read of K step kt has
+    // been issued: wait for the DMA of kt + 1, barrier (now every wave has left the stage of kt), and
+    // start the DMA of K step kt + NSTAGE into that stage.  Every K step issues the same number of DMA
+    // instructions (beyond the end the last step is loaded again into a stage nobody reads), so the
+    // wait count is a constant: the NSTAGE - 2 newest groups may still be in flight.
+    const int KT = kb / RB;
+#pragma unroll
+    for (int st = 0; st < NSTAGE; ++st) issue(st, min(st, KT - 1));
+    wait_vm<(NSTAGE - 1) * CH>();
     lds_barrier();
-
-    // One K step: start the DMA two steps ahead (into the stage consumed in the previous step, which
-    // every wave has left), consume the current stage, then wait until the next stage has landed for
-    // every wave.
-    int cur = 0;
-    for (int kt = 0; kt < KT; ++kt) {
-        const bool more = kt + 2 < KT;
-        if (more) issue(cur == 0 ? 2 : cur - 1, kt + 2);
-        compute(smem + cur * STAGE);
-        if (more) wait_vm<CH>(); else wait_vm<0>();
-        lds_barrier();
-        cur = (cur == 2) ? 0 : cur + 1;
+    Frags raw[2];
+    Unpacked unp[2];
+    load_frags(raw[0], smem, 0);
+    load_frags(raw[1], smem, 1);
+    unpack(raw[0], unp[0]);
+    int cur = 0;                    // stage of K step kt
+    for (int kt = 0; kt + 1 < KT; ++kt) {
+        const int nxt = (cur == NSTAGE - 1) ? 0 : cur + 1;
+        const unsigned char* scur = smem + cur * STAGE;
+        const unsigned char* snxt = smem + nxt * STAGE;
+#pragma unroll
+        for (int s = 0; s < NSUB; ++s) {
+            if (s == NSUB - 2) {
+                wait_vm<(NSTAGE - 2) * CH>();
+                lds_barrier();      // stage nxt has landed for every wave; every wave has left stage cur
+                issue(cur, min(kt + NSTAGE, KT - 1));
+            }
+            if (s + 2 < NSUB) load_frags(raw[s & 1], scur, s + 2);
+            else load_frags(raw[s & 1], snxt, s + 2 - NSUB);
+            unpack(raw[(s + 1) & 1], unp[(s + 1) & 1]);
+            mfma_all(unp[s & 1]);
+            interleave(true);
+        }
+        cur = nxt;
     }
+    {
+        const unsigned char* scur = smem + cur * STAGE;
+#pragma unroll
+        for (int s = 0; s < NSUB; ++s) {
+            if (s + 2 < NSUB) load_frags(raw[s & 1], scur, s + 2);
+            if (s + 1 < NSUB) unpack(raw[(s + 1) & 1], unp[(s + 1) & 1]);
+            mfma_all(unp[s & 1]);
+            interleave(s + 2 < NSUB);
+        }
+    }
+    wait_vm<0>();
+    lds_barrier();
 
     // ---- epilogue.  Accumulator element e of block (i, j): output channel
     // n0 + wn WN + 32 j + 8 (e / 4) + 4 fk + e % 4, token m0 + wm WM + 32 i + frow.
@@ -230,10 +291,10 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
             const int tbase = m0 + wm * WM + 32 * i, nbase = n0 + wn * WN;
             if (vec_store) {
-                constexpr int CPR = WN / 8;                   // 16-byte chunks per slab row
+                constexpr int CPS = WN / 8;                   // 16-byte chunks per slab row
 #pragma unroll
-                for (int c = lane; c < 32 * CPR; c += 64) {
-                    const int row = c / CPR, col = (c % CPR) * 8;
+                for (int c = lane; c < 32 * CPS; c += 64) {
+                    const int row = c / CPS, col = (c % CPS) * 8;
                     const u32x4 v = *reinterpret_cast<const u32x4*>(slab + row * (WN * 2) + col * 2);
                     if (tbase + row < T && nbase + col < N)
                         *reinterpret_cast<u32x4*>(y + (int64_t)(tbase + row) * ldo + nbase + col) = v;
@@ -251,24 +312,24 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     }
 }
 
-template <int BM, int BN, int WGM, int WGN>
+template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE>
 pme_status launch_tile(const GemmArgs& a) {
-    const int tiles_m = (int)((a.T + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     const int kb = (int)(a.d_e / 2);
+    if (kb % RB) return PME_ERR_UNSUPPORTED_PATH;
+    const int tiles_m = (int)((a.T + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WGM * WGN);
-    const size_t lds = 3 * (size_t)(BM + BN) * kRowBytes;
+    const size_t lds = (size_t)NSTAGE * (BM + BN) * RB;
     if (lds > 64 * 1024) {
-        // one attribute call per instantiation and mode is enough, but the call is cheap and idempotent
-        hipError_t e0 = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WGM, WGN, MODE_BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipError_t e1 = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WGM, WGN, MODE_ASYM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipError_t e2 = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WGM, WGN, MODE_I32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e0 = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e1 = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_ASYM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        hipError_t e2 = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_I32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
         if (e0 != hipSuccess || e1 != hipSuccess || e2 != hipSuccess) return PME_ERR_HIP;
     }
     // 16-byte output pieces need 8-element alignment of N, the pitch and the base
     const int vec = (a.N % 8 == 0 && a.ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0) ? 1 : 0;
-#define PME_LAUNCH(MODE)                                                                                      \
-    hipLaunchKernelGGL((k_gemm_mfma<BM, BN, WGM, WGN, MODE>), grid, block, lds, a.stream, a.qx, a.qw, a.sx, a.sw, \
-                       a.zx, a.wsum, (int)a.T, (int)a.N, kb, a.y, a.ldy, tiles_m, tiles_n, vec)
+#define PME_LAUNCH(MODE)                                                                                        \
+    hipLaunchKernelGGL((k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE>), grid, block, lds, a.stream, a.qx, a.qw, \
+                       a.sx, a.sw, a.zx, a.wsum, (int)a.T, (int)a.N, kb, a.y, a.ldy, tiles_m, tiles_n, vec)
     if (a.out_i32) PME_LAUNCH(MODE_I32);
     else if (a.zx) PME_LAUNCH(MODE_ASYM);
     else PME_LAUNCH(MODE_BF16);
@@ -284,32 +345,43 @@ void set_gemm_tile_override(int id) { g_tile_override = id; }
 
 pme_status launch_gemm_mfma(const GemmArgs& a) {
     // d_e a multiple of 128 (whole K steps), 16-byte aligned rows, and the x256 accumulator in range.
-    if (a.d_e % 128 || a.d_e > (1 << 17)) return PME_ERR_UNSUPPORTED_PATH;
+    if (a.d_e % 128 || a.d_e > (1 << 17)) return PME_ERR_UNSUPPORTED_PATH;   // tiles with 128-byte rows need d_e % 256 == 0
     if ((reinterpret_cast<uintptr_t>(a.qx) & 15) || (reinterpret_cast<uintptr_t>(a.qw) & 15)) return PME_ERR_UNSUPPORTED_PATH;
     if (a.zx && a.out_i32) return PME_ERR_UNSUPPORTED_PATH;
     const int64_t cus = 256;
     auto tiles = [&](int bm, int bn) { return ((a.T + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
     int id = g_tile_override;
     if (id == 0) {
-        // the largest tile that still gives every one of the 256 compute units a workgroup
-        if (tiles(256, 256) >= cus) id = 1;
-        else if (tiles(128, 256) >= cus) id = 2;
-        else if (tiles(128, 192) >= cus) id = 3;
-        else if (tiles(128, 128) >= cus) id = 4;
+        // The largest tile that still gives every one of the 256 compute units a workgroup; whole
+        // 128-byte lines per row and K step where d_e allows (measured faster on MI355X).
+        const bool wide = (a.d_e % 256) == 0;
+        if (tiles(256, 256) >= cus) id = wide ? 11 : 8;
+        else if (tiles(128, 256) >= cus) id = wide ? 16 : 2;
+        else if (tiles(128, 192) >= cus) id = wide ? 15 : 9;
+        else if (tiles(128, 128) >= cus) id = wide ? 13 : 4;
         else if (tiles(64, 128) >= cus / 2) id = 6;
         else id = 7;
     }
     switch (id) {
-        case 1: return launch_tile<256, 256, 2, 4>(a);     // 8 waves of 128 x 64
-        case 2: return launch_tile<128, 256, 2, 4>(a);     // 8 waves of 64 x 64
-        case 3: return launch_tile<128, 192, 4, 2>(a);     // 8 waves of 32 x 96
-        case 4: return launch_tile<128, 128, 2, 4>(a);     // 8 waves of 64 x 32
-        case 5: return launch_tile<128, 128, 2, 2>(a);     // 4 waves of 64 x 64
-        case 6: return launch_tile<64, 128, 2, 2>(a);      // 4 waves of 32 x 64
-        case 7: return launch_tile<64, 64, 2, 2>(a);       // 4 waves of 32 x 32
-        case 8: return launch_tile<256, 256, 2, 2>(a);     // 4 waves of 128 x 128
-        case 9: return launch_tile<128, 192, 2, 2>(a);     // 4 waves of 64 x 96
-        case 10: return launch_tile<256, 128, 4, 2>(a);    // 8 waves of 64 x 64
+        case 1: return launch_tile<256, 256, 2, 4, 64, 3>(a);      // 8 waves of 128 x 64
+        case 2: return launch_tile<128, 256, 2, 4, 64, 3>(a);      // 8 waves of 64 x 64
+        case 3: return launch_tile<128, 192, 4, 2, 64, 3>(a);      // 8 waves of 32 x 96
+        case 4: return launch_tile<128, 128, 2, 4, 64, 3>(a);      // 8 waves of 64 x 32
+        case 5: return launch_tile<128, 128, 2, 2, 64, 3>(a);      // 4 waves of 64 x 64
+        case 6: return launch_tile<64, 128, 2, 2, 64, 3>(a);       // 4 waves of 32 x 64
+        case 7: return launch_tile<64, 64, 2, 2, 64, 3>(a);        // 4 waves of 32 x 32
+        case 8: return launch_tile<256, 256, 2, 2, 64, 3>(a);      // 4 waves of 128 x 128
+        case 9: return launch_tile<128, 192, 2, 2, 64, 3>(a);      // 4 waves of 64 x 96
+        case 10: return launch_tile<256, 128, 4, 2, 64, 3>(a);     // 8 waves of 64 x 64
+        // whole 128-byte lines per row and K step
+        case 11: return launch_tile<256, 256, 2, 2, 128, 2>(a);    // 4 waves of 128 x 128
+        case 12: return launch_tile<256, 256, 2, 4, 128, 2>(a);    // 8 waves of 128 x 64
+        case 13: return launch_tile<128, 128, 2, 2, 128, 3>(a);    // 4 waves of 64 x 64
+        case 14: return launch_tile<128, 128, 2, 4, 128, 3>(a);    // 8 waves of 64 x 32
+        case 15: return launch_tile<128, 192, 2, 2, 128, 3>(a);    // 4 waves of 64 x 96
+        case 16: return launch_tile<128, 256, 2, 4, 128, 3>(a);    // 8 waves of 64 x 64
+        case 17: return launch_tile<256, 128, 4, 2, 128, 3>(a);    // 8 waves of 64 x 64
+        case 18: return launch_tile<256, 128, 2, 2, 128, 3>(a);    // 4 waves of 128 x 64
     }
     return PME_ERR_UNSUPPORTED_PATH;
 }

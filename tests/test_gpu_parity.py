@@ -154,6 +154,33 @@ def test_gemm_accumulators_and_epilogue(name, T, N, d_e, paths):
         check_bf16(y, y_ref)
 
 
+@pytest.mark.parametrize("tile", range(1, 19))
+def test_gemm_every_tile_configuration(tile):
+    # every entry of the MFMA kernel's tile table, forced through the tuning hook: ragged T and N,
+    # 5 K steps of 128 bytes (10 of 64), extreme rows
+    rng = np.random.default_rng(tile)
+    T, N, d_e = 300, 520, 1280
+    q = rng.integers(-7, 8, size=(T, d_e), dtype=np.int8)
+    qw = rng.integers(-8, 8, size=(N, d_e), dtype=np.int8)
+    q[0] = -7
+    qw[1] = -8
+    sx = rng.uniform(0.01, 2.0, T).astype(np.float32)
+    sw = rng.uniform(0.001, 0.01, N).astype(np.float32)
+    acc_ref = oracle.int_gemm(q, qw)
+    qd = torch.from_numpy(oracle.pack_int4(q)).cuda()
+    wd = torch.from_numpy(oracle.pack_int4(qw)).cuda()
+    pme.set_path(MFMA)
+    pme.set_gemm_tile(tile)
+    try:
+        acc = pme.w4a4_gemm_i32(qd, wd).cpu().numpy()
+        y = pme.w4a4_gemm(qd, torch.from_numpy(sx).cuda(), wd, torch.from_numpy(sw).cuda())
+        y = y.to(torch.float32).cpu().numpy()
+    finally:
+        pme.set_gemm_tile(0)
+    assert np.array_equal(acc, acc_ref)
+    check_bf16(y, oracle.dequant_bf16(acc_ref, sx, sw))
+
+
 @pytest.mark.parametrize("path", (GENERIC, MFMA))
 def test_gemm_asymmetric(path):
     rng = np.random.default_rng(8)
