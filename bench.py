@@ -68,6 +68,9 @@ def main() -> int:
     ap.add_argument("--workload", default="C2", help="C1..C5 (default C2, the configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", action="store_true", help="also time each stage and every other workload")
+    ap.add_argument("--probe-copy", action="store_true",
+                    help="also run the library's plain 1 GiB copy kernel (the known-size dispatch that calibrates "
+                         "the profiler's FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -131,11 +134,17 @@ def main() -> int:
         ach = ops / (t_gemm * 1e-3) / 1e12
         roof = {"bound": "mfma", "kernel": "w4a4_gemm", "achieved": ach, "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s",
                 "frac": ach / PEAK_INT8_TOPS, "traffic": None, "avg_launch_us": t_gemm * 1e3,
+                "algorithmic_ops": ops, "algorithmic_bytes": algorithmic_bytes_gemm(sp),
                 "note": "int8 MFMA ops (2 per multiply-add) over the expanded d_e"}
     traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
     if os.path.exists(traffic_file):
         with open(traffic_file) as f:
-            roof["traffic"] = json.load(f).get(sp.name, {}).get("w4a4_gemm")
+            tr = json.load(f).get(sp.name, {}).get("w4a4_gemm")
+        if tr:
+            # HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), calibrated by the
+            # library's 1 GiB copy kernel; see profiles/expanded_linear_<workload>.md
+            roof["traffic"] = tr["total_bytes"]
+            roof["traffic_detail"] = tr
     rot_bytes = algorithmic_bytes_rotate_quant(sp)
     rot_gbs = rot_bytes / (t_rot * 1e-3) / 1e9
 
@@ -173,6 +182,15 @@ def main() -> int:
             del wl2, b2
             torch.cuda.empty_cache()
         out["other_workloads"] = others
+    if args.probe_copy:
+        src = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            pme.probe_copy(src, dst)
+        t_copy = _event_ms(lambda: pme.probe_copy(src, dst), 5)
+        out["probe_copy"] = {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "us": t_copy * 1e3,
+                             "gbs": 2 * (1 << 30) / (t_copy * 1e-3) / 1e9}
+        del src, dst
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(wl)
     print(json.dumps(out))

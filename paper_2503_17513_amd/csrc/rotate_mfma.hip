@@ -18,6 +18,7 @@
 // Waves split the token by a' (16-wide tiles, TPW tiles per wave); the FWHT never crosses a'.
 #include "pme_internal.h"
 
+#include <algorithm>
 #include <mutex>
 
 namespace pme {
@@ -210,9 +211,26 @@ template <int MT> __device__ __forceinline__ int chunk_of(int a, int c) {
     return ((a >> 2) * MT + (c >> 4)) * 8 + (a & 3) * 2 + ((c >> 3) & 1);
 }
 
+// LDS-only barrier and DMA helpers.  The DMA and the waits on it are inline assembly so that the
+// compiler does not order LDS reads of the B fragments or of the reduction scratch after them.
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+__device__ __forceinline__ void wait_all_vm() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// 16 bytes per lane from global memory into LDS at lds_base + 16 * lane (lds_base wave-uniform); lanes
+// switched off by the caller's branch move nothing.  Overwrites M0, which the compiler does not keep
+// values in; no other code in this kernel makes the compiler emit an M0 use.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+}
+
+// One workgroup handles tokens blockIdx.x, blockIdx.x + gridDim.x, ...  The token buffer in LDS is
+// refilled for the next token as soon as the matrix-core phase of the current one has consumed it,
+// so the HBM read of token i + 1 runs under the FWHT / quantize / store phase of token i.
+// Most waves a workgroup of this instantiation is launched with (bounds the registers per lane).
+template <int KLOG2, int TPW> constexpr int max_waves() { return (TPW == 1 && KLOG2 <= 8) ? kMaxWaves : kMaxWaves / 2; }
+
 template <int KLOG2, int TPW, bool F32IN>
-__global__ void __launch_bounds__(64 * kMaxWaves)
-k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int d, int d_e, int b, int ks_count, int slot,
+__global__ void __launch_bounds__((64 * max_waves<KLOG2, TPW>()))
+k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, int b, int ks_count, int slot,
               double gamma, uint8_t* __restrict__ qx, float* __restrict__ sx, int32_t* __restrict__ zx,
               float* __restrict__ xhat) {
     using L = Layout<KLOG2>;
@@ -220,30 +238,27 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int d, int d_e, int b, i
     constexpr int NS = F32IN ? 3 : 1;
     const int plane_bytes = ks_count * MT * 1024;     // one bf16 copy of the K-padded token
 
-    extern __shared__ __align__(16) unsigned char smem[];   // NS * plane_bytes
+    extern __shared__ __align__(1024) unsigned char smem[];   // NS token planes, then the B fragments
     __shared__ float red[2 * kMaxWaves];
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nwaves = blockDim.x >> 6, nthreads = blockDim.x;
-    const int64_t t = blockIdx.x;
     const int l15 = lane & 15, g = lane >> 4;
     const int rows_k = 32 * ks_count;                 // rows of the K-padded operand
+    const int ntiles = (b + 15) >> 4;
+    unsigned char* bsm = smem + NS * plane_bytes + (size_t)wave * TPW * ks_count * 1024;   // this wave's B fragments
 
+    // ---- once per workgroup: B fragments of P into LDS, zero padding of the token buffer
+#pragma unroll
+    for (int ti = 0; ti < TPW; ++ti) {
+        const int tile = min(wave * TPW + ti, kMaxTiles - 1);
+        for (int ks = 0; ks < ks_count; ++ks)
+            *reinterpret_cast<u32x4*>(bsm + ((size_t)(ti * ks_count + ks) * 64 + lane) * 16) = g_ptable[slot][tile * kMaxKs + ks][lane];
+    }
+    const int real_groups = (((d + NC - 1) >> KLOG2) + 3) >> 2;        // 4-row groups holding real inputs
+    const int nchunks = real_groups * MT * 8;
     if constexpr (!F32IN) {
-        // ---- 1a. bf16 token: HBM -> LDS by DMA, 16 bytes per lane, laid out for transposing reads.
-        const unsigned char* xr = reinterpret_cast<const unsigned char*>(static_cast<const uint16_t*>(xv) + t * ldx);
-        const int real_groups = (((d + NC - 1) >> KLOG2) + 3) >> 2;        // 4-row groups holding real inputs
-        const int nchunks = real_groups * MT * 8;
-        for (int base = wave * 64; base < nchunks; base += nwaves * 64) {
-            const int p = base + lane;
-            const int blk = p >> 3, r = p & 7;
-            const int a = 4 * (blk / MT) + (r >> 1), c = 16 * (blk % MT) + 8 * (r & 1);
-            const int i = a * NC + c;
-            if (p < nchunks && i < d)
-                __builtin_amdgcn_global_load_lds((const PME_AS1 void*)(xr + 2 * (size_t)i),
-                                                 (PME_AS3 void*)(smem + (size_t)base * 16), 16, 0, 0);
-        }
-        // chunks of the K-padded operand that hold no input are zero
+        // chunks of the K-padded operand that hold no input are zero and are never written again
         const int first = ((d >> KLOG2) >> 2) * MT * 8;
         const int total = (rows_k >> 2) * MT * 8;
         for (int p = first + tid; p < total; p += nthreads) {
@@ -251,10 +266,24 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int d, int d_e, int b, i
             const int a = 4 * (blk / MT) + (r >> 1), c = 16 * (blk % MT) + 8 * (r & 1);
             if (a * NC + c >= d) *reinterpret_cast<u32x4*>(smem + (size_t)p * 16) = u32x4{0u, 0u, 0u, 0u};
         }
-    } else {
-        // ---- 1b. fp32 token: split every input into three bf16 terms (exact sum) and store each term
-        //          plane in A-fragment order: fragment (ks, mt), slot (c % 16) + 16 g holds the 8 values
-        //          a = 32 ks + 8 g + e of column c = 16 mt + c % 16.
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(PME_AS3 unsigned char*)smem;
+
+    // bf16 token: HBM -> LDS by DMA, 16 bytes per lane, laid out for the transposing reads
+    auto load_token_dma = [&](int64_t t) {
+        const unsigned char* xr = reinterpret_cast<const unsigned char*>(static_cast<const uint16_t*>(xv) + t * ldx);
+        for (int base = wave * 64; base < nchunks; base += nwaves * 64) {
+            const int p = base + lane;
+            const int blk = p >> 3, r = p & 7;
+            const int a = 4 * (blk / MT) + (r >> 1), c = 16 * (blk % MT) + 8 * (r & 1);
+            const int i = a * NC + c;
+            if (p < nchunks && i < d) dma16(xr + 2 * (size_t)i, __builtin_amdgcn_readfirstlane(lds0 + base * 16));
+        }
+    };
+    // fp32 token: split every input into three bf16 terms (exact sum) and store each term plane in
+    // A-fragment order: fragment (ks, mt), slot (c % 16) + 16 g holds the 8 values a = 32 ks + 8 g + e of
+    // column c = 16 mt + c % 16.
+    auto load_token_f32 = [&](int64_t t) {
         const float* xr = static_cast<const float*>(xv) + t * ldx;
         const int units = ks_count * 4 * NC;
         for (int u = tid; u < units; u += nthreads) {
@@ -283,182 +312,199 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int d, int d_e, int b, i
             *reinterpret_cast<u32x4*>(dst + plane_bytes) = p1;
             *reinterpret_cast<u32x4*>(dst + 2 * plane_bytes) = p2;
         }
+    };
+
+    int64_t t = blockIdx.x;
+    if constexpr (!F32IN) {
+        if (t < T) load_token_dma(t);
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);     // vmcnt(0): the DMA writes have landed
-    __syncthreads();
+    const int l4 = (lane >> 4) & 1, l5 = lane >> 5;
+    const int c0 = run_start<KLOG2>(l4, l5);
 
-    // ---- 2. base block on the matrix cores: Z^T[c][a'] = sum_a X~[a][c] P[a][a']
-    f32x4 acc[TPW][MT];
-#pragma unroll
-    for (int ti = 0; ti < TPW; ++ti)
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) acc[ti][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    const int ntiles = (b + 15) >> 4;
-    for (int ks = 0; ks < ks_count; ++ks) {
-        bf16x8 bfrag[TPW];
-#pragma unroll
-        for (int ti = 0; ti < TPW; ++ti) {
-            const int tile = min(wave * TPW + ti, kMaxTiles - 1);
-            bfrag[ti] = __builtin_bit_cast(bf16x8, g_ptable[slot][tile * kMaxKs + ks][lane]);
+    for (; t < T; t += gridDim.x) {
+        if constexpr (F32IN) {
+            lds_barrier();                  // every wave has finished reading the previous token
+            load_token_f32(t);
+        } else {
+            wait_all_vm();                  // this wave's part of the token (and its earlier stores) has landed
         }
+        lds_barrier();
+
+        // ---- base block on the matrix cores: Z^T[c][a'] = sum_a X~[a][c] P[a][a']
+        f32x4 acc[TPW][MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-            if constexpr (!F32IN) {
-                // two transposing reads: lane (g, j = lane % 16) addresses 8 bytes of row 32 ks + 8 g + 4 h + j / 4
-                // and receives rows 32 ks + 8 g + 4 h + (0..3) of column 16 mt + j.
-                const unsigned char* p0 = smem + ((size_t)((8 * ks + 2 * g) * MT + mt)) * 128 + 8 * l15;
-                const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 PME_AS3*)p0);
-                const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 PME_AS3*)(p0 + MT * 128));
-                typedef __attribute__((ext_vector_type(8))) short s16x8;
-                const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                const bf16x8 af = __builtin_bit_cast(bf16x8, both);
+        for (int ti = 0; ti < TPW; ++ti)
 #pragma unroll
-                for (int ti = 0; ti < TPW; ++ti)
-                    if ((wave * TPW + ti) < ntiles)
-                        acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfrag[ti], acc[ti][mt], 0, 0, 0);
-            } else {
+            for (int mt = 0; mt < MT; ++mt) acc[ti][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+        for (int ks = 0; ks < ks_count; ++ks) {
+            bf16x8 bfrag[TPW];
 #pragma unroll
-                for (int sp = 0; sp < NS; ++sp) {
-                    const u32x4 raw = *reinterpret_cast<const u32x4*>(
-                        smem + (size_t)sp * plane_bytes + ((size_t)((ks * MT + mt) * 64 + lane)) * 16);
-                    const bf16x8 af = __builtin_bit_cast(bf16x8, raw);
+            for (int ti = 0; ti < TPW; ++ti)
+                bfrag[ti] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(bsm + ((size_t)(ti * ks_count + ks) * 64 + lane) * 16));
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                if constexpr (!F32IN) {
+                    // two transposing reads: lane (g, j = lane % 16) addresses 8 bytes of row 32 ks + 8 g + 4 h + j / 4
+                    // and receives rows 32 ks + 8 g + 4 h + (0..3) of column 16 mt + j.
+                    const unsigned char* p0 = smem + ((size_t)((8 * ks + 2 * g) * MT + mt)) * 128 + 8 * l15;
+                    const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 PME_AS3*)p0);
+                    const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 PME_AS3*)(p0 + MT * 128));
+                    typedef __attribute__((ext_vector_type(8))) short s16x8;
+                    const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    const bf16x8 af = __builtin_bit_cast(bf16x8, both);
 #pragma unroll
                     for (int ti = 0; ti < TPW; ++ti)
                         if ((wave * TPW + ti) < ntiles)
                             acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfrag[ti], acc[ti][mt], 0, 0, 0);
+                } else {
+#pragma unroll
+                    for (int sp = 0; sp < NS; ++sp) {
+                        const u32x4 raw = *reinterpret_cast<const u32x4*>(
+                            smem + (size_t)sp * plane_bytes + ((size_t)((ks * MT + mt) * 64 + lane)) * 16);
+                        const bf16x8 af = __builtin_bit_cast(bf16x8, raw);
+#pragma unroll
+                        for (int ti = 0; ti < TPW; ++ti)
+                            if ((wave * TPW + ti) < ntiles)
+                                acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfrag[ti], acc[ti][mt], 0, 0, 0);
+                    }
                 }
             }
         }
-    }
 
-    // ---- 3. FWHT along c, in registers
-    float v[TPW][NREG];
-#pragma unroll
-    for (int ti = 0; ti < TPW; ++ti) {
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int r = 0; r < 4; ++r) v[ti][mt * 4 + r] = acc[ti][mt][r];
-        if ((wave * TPW + ti) < ntiles) fwht_lane<KLOG2>(v[ti]);
-    }
+        if constexpr (!F32IN) {
+            // every wave has read the token out of LDS: refill the buffer with the next token now
+            lds_barrier();
+            if (t + gridDim.x < T) load_token_dma(t + gridDim.x);
+        }
 
-    const int l4 = (lane >> 4) & 1, l5 = lane >> 5;
-    const int c0 = run_start<KLOG2>(l4, l5);
+        // ---- FWHT along c, in registers
+        float v[TPW][NREG];
+#pragma unroll
+        for (int ti = 0; ti < TPW; ++ti) {
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+                for (int r = 0; r < 4; ++r) v[ti][mt * 4 + r] = acc[ti][mt][r];
+            if ((wave * TPW + ti) < ntiles) fwht_lane<KLOG2>(v[ti]);
+        }
 
-    if (xhat) {
-        const float gf = (float)gamma;
+        if (xhat) {
+            const float gf = (float)gamma;
+#pragma unroll
+            for (int ti = 0; ti < TPW; ++ti) {
+                const int ap = (wave * TPW + ti) * 16 + l15;
+                if (ap < b) {
+                    float* o = xhat + t * d_e + (int64_t)ap * NC + c0;
+#pragma unroll
+                    for (int j = 0; j < L::RUN; ++j) o[j] = v[ti][L::reg_of_run_pos(j)] * gf;
+                }
+            }
+        }
+        if (!qx) continue;
+
+        // ---- per-token range
+        float hi = 0.f, lo = 0.f;
+        if (zx) {
+#pragma unroll
+            for (int ti = 0; ti < TPW; ++ti)
+#pragma unroll
+                for (int i = 0; i < NREG; ++i) {
+                    hi = fmaxf(hi, v[ti][i]);
+                    lo = fminf(lo, v[ti][i]);
+                }
+            lo = wave_min(lo);
+        } else {
+#pragma unroll
+            for (int ti = 0; ti < TPW; ++ti)
+#pragma unroll
+                for (int i = 0; i < NREG; i += 2) hi = __builtin_fmaxf(__builtin_fmaxf(hi, __builtin_fabsf(v[ti][i])), __builtin_fabsf(v[ti][i + 1]));
+        }
+        hi = wave_max(hi);
+        if (nwaves > 1) {
+            // the scratch is reused per token: the barrier of the matrix phase separates the tokens
+            if (lane == 0) { red[wave] = hi; red[kMaxWaves + wave] = lo; }
+            lds_barrier();
+            for (int w = 0; w < nwaves; ++w) {
+                hi = fmaxf(hi, red[w]);
+                lo = fminf(lo, red[kMaxWaves + w]);
+            }
+        }
+
+        float s = 1.f, rinv = 0.f;
+        int z = 0;
+        if (!zx) {
+            if (hi > 0.f) {
+                s = (float)((double)hi * gamma / 7.0);
+                rinv = (float)(gamma / (double)s);
+            }
+            if (tid == 0) sx[t] = s;
+        } else {
+            if (hi > lo) {
+                s = (float)(((double)hi - (double)lo) * gamma / 15.0);
+                rinv = (float)(gamma / (double)s);
+                z = (int)rint(-(double)lo * gamma / (double)s);
+                z = min(15, max(0, z));
+            }
+            if (tid == 0) { sx[t] = s; zx[t] = z; }
+        }
+
+        // ---- round, pack, store.
+        // fma(u, rinv, 1.5 * 2^23 + 8) has the bit pattern C + e with C = 0x4B400000 and e = rne(u * rinv) + 8
+        // in [1, 15].  Eight of them are combined by Horner steps acc = (acc << 4) + bits; the digits are
+        // non-negative, so no carries cross nibbles, and the accumulated constant C * 0x11111111 is
+        // subtracted once.  e ^ 8 is the 4-bit two's-complement code.
+        constexpr uint32_t kC = 0x4B400000u;
+        constexpr uint32_t kCsum = kC * 0x11111111u;
 #pragma unroll
         for (int ti = 0; ti < TPW; ++ti) {
             const int ap = (wave * TPW + ti) * 16 + l15;
+            uint32_t words[L::RUN / 8];
+#pragma unroll
+            for (int wd = 0; wd < L::RUN / 8; ++wd) {
+                if (!zx) {
+                    uint32_t accw = 0;
+#pragma unroll
+                    for (int nb = 7; nb >= 0; --nb) {
+                        const float f = __builtin_fmaf(v[ti][L::reg_of_run_pos(wd * 8 + nb)], rinv, 12582920.f);
+                        accw = (accw << 4) + __float_as_uint(f);
+                    }
+                    words[wd] = (accw - kCsum) ^ 0x88888888u;
+                } else {
+                    uint32_t accw = 0;
+#pragma unroll
+                    for (int nb = 7; nb >= 0; --nb) {
+                        const float f = __builtin_fmaf(v[ti][L::reg_of_run_pos(wd * 8 + nb)], rinv, 12582912.f);
+                        int code = (int)(__float_as_uint(f) - kC) + z;
+                        code = min(15, max(0, code));
+                        accw = (accw << 4) + (uint32_t)code;
+                    }
+                    words[wd] = accw;
+                }
+            }
             if (ap < b) {
-                float* o = xhat + t * d_e + (int64_t)ap * NC + c0;
+                uint8_t* o = qx + t * (int64_t)(d_e / 2) + (((int64_t)ap * NC + c0) >> 1);
+                if constexpr (L::RUN / 8 == 1) {
+                    *reinterpret_cast<uint32_t*>(o) = words[0];
+                } else if constexpr (L::RUN / 8 == 2) {
+                    *reinterpret_cast<u32x2*>(o) = u32x2{words[0], words[1]};
+                } else {
 #pragma unroll
-                for (int j = 0; j < L::RUN; ++j) o[j] = v[ti][L::reg_of_run_pos(j)] * gf;
-            }
-        }
-    }
-    if (!qx) return;
-
-    // ---- 4. per-token range
-    float hi = 0.f, lo = 0.f;
-    if (zx) {
-#pragma unroll
-        for (int ti = 0; ti < TPW; ++ti)
-#pragma unroll
-            for (int i = 0; i < NREG; ++i) {
-                hi = fmaxf(hi, v[ti][i]);
-                lo = fminf(lo, v[ti][i]);
-            }
-        lo = wave_min(lo);
-    } else {
-#pragma unroll
-        for (int ti = 0; ti < TPW; ++ti)
-#pragma unroll
-            for (int i = 0; i < NREG; i += 2) hi = fmaxf(hi, fmaxf(fabsf(v[ti][i]), fabsf(v[ti][i + 1])));
-    }
-    hi = wave_max(hi);
-    if (nwaves > 1) {
-        if (lane == 0) { red[wave] = hi; red[kMaxWaves + wave] = lo; }
-        __syncthreads();
-        for (int w = 0; w < nwaves; ++w) {
-            hi = fmaxf(hi, red[w]);
-            lo = fminf(lo, red[kMaxWaves + w]);
-        }
-    }
-
-    float s = 1.f, rinv = 0.f;
-    int z = 0;
-    if (!zx) {
-        if (hi > 0.f) {
-            s = (float)((double)hi * gamma / 7.0);
-            rinv = (float)(gamma / (double)s);
-        }
-        if (tid == 0) sx[t] = s;
-    } else {
-        if (hi > lo) {
-            s = (float)(((double)hi - (double)lo) * gamma / 15.0);
-            rinv = (float)(gamma / (double)s);
-            z = (int)rint(-(double)lo * gamma / (double)s);
-            z = min(15, max(0, z));
-        }
-        if (tid == 0) { sx[t] = s; zx[t] = z; }
-    }
-
-    // ---- 5. round, pack, store.
-    // fma(u, rinv, 1.5 * 2^23 + 8) has the bit pattern C + e with C = 0x4B400000 and e = rne(u * rinv) + 8
-    // in [1, 15].  Eight of them are combined by Horner steps acc = (acc << 4) + bits; the digits are
-    // non-negative, so no carries cross nibbles, and the accumulated constant C * 0x11111111 is
-    // subtracted once.  e ^ 8 is the 4-bit two's-complement code.
-    constexpr uint32_t kC = 0x4B400000u;
-    constexpr uint32_t kCsum = kC * 0x11111111u;
-#pragma unroll
-    for (int ti = 0; ti < TPW; ++ti) {
-        const int ap = (wave * TPW + ti) * 16 + l15;
-        uint32_t words[L::RUN / 8];
-#pragma unroll
-        for (int wd = 0; wd < L::RUN / 8; ++wd) {
-            if (!zx) {
-                uint32_t accw = 0;
-#pragma unroll
-                for (int nb = 7; nb >= 0; --nb) {
-                    const float f = __builtin_fmaf(v[ti][L::reg_of_run_pos(wd * 8 + nb)], rinv, 12582920.f);
-                    accw = (accw << 4) + __float_as_uint(f);
+                    for (int wd = 0; wd < L::RUN / 8; wd += 4)
+                        *reinterpret_cast<u32x4*>(o + 4 * wd) = u32x4{words[wd], words[wd + 1], words[wd + 2], words[wd + 3]};
                 }
-                words[wd] = (accw - kCsum) ^ 0x88888888u;
-            } else {
-                uint32_t accw = 0;
-#pragma unroll
-                for (int nb = 7; nb >= 0; --nb) {
-                    const float f = __builtin_fmaf(v[ti][L::reg_of_run_pos(wd * 8 + nb)], rinv, 12582912.f);
-                    int code = (int)(__float_as_uint(f) - kC) + z;
-                    code = min(15, max(0, code));
-                    accw = (accw << 4) + (uint32_t)code;
-                }
-                words[wd] = accw;
-            }
-        }
-        if (ap < b) {
-            uint8_t* o = qx + t * (int64_t)(d_e / 2) + (((int64_t)ap * NC + c0) >> 1);
-            if constexpr (L::RUN / 8 == 1) {
-                *reinterpret_cast<uint32_t*>(o) = words[0];
-            } else if constexpr (L::RUN / 8 == 2) {
-                *reinterpret_cast<u32x2*>(o) = u32x2{words[0], words[1]};
-            } else {
-#pragma unroll
-                for (int wd = 0; wd < L::RUN / 8; wd += 4)
-                    *reinterpret_cast<u32x4*>(o + 4 * wd) = u32x4{words[wd], words[wd + 1], words[wd + 2], words[wd + 3]};
             }
         }
     }
+    wait_all_vm();
 }
 
 template <int KLOG2, int TPW, bool F32IN>
 pme_status launch_one(const RotateArgs& a, int ks, int nwaves) {
     using L = Layout<KLOG2>;
     constexpr int NS = F32IN ? 3 : 1;
-    const size_t lds = (size_t)NS * ks * L::MT * 1024;
-    if (lds + 256 > 160 * 1024) return PME_ERR_UNSUPPORTED_PATH;
+    const size_t lds = (size_t)NS * ks * L::MT * 1024 + (size_t)nwaves * TPW * ks * 1024;
+    if (lds + 256 > 160 * 1024 || nwaves > max_waves<KLOG2, TPW>()) return PME_ERR_UNSUPPORTED_PATH;
     const int rows = (int)((a.d + L::NC - 1) >> KLOG2);
     pme_status st = PME_OK;
     const int slot = table_slot(a.b, rows, a.stream, &st);
@@ -468,13 +514,23 @@ pme_status launch_one(const RotateArgs& a, int ks, int nwaves) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return PME_ERR_HIP;
     }
+    // Persistent grid: as many workgroups as fit on the 256 compute units at once (LDS, and about 12
+    // waves per compute unit at this register use), preferring a count that divides the tokens evenly.
+    int occ = (int)((160 * 1024) / (lds + 1024));
+    occ = std::min(occ, 12 / nwaves);
+    occ = std::max(1, std::min(occ, 8));
+    const unsigned grid = (unsigned)std::min<int64_t>(a.T, 256 * (int64_t)occ);
     const double gamma = 1.0 / sqrt((double)a.d_e);
-    hipLaunchKernelGGL(kern, dim3((unsigned)a.T), dim3(64 * nwaves), lds, a.stream, a.x, a.ldx, (int)a.d,
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * nwaves), lds, a.stream, a.x, a.ldx, (int)a.T, (int)a.d,
                        (int)a.d_e, a.b, ks, slot, gamma, a.qx, a.sx, a.zx, a.xhat);
     return hip_status(hipGetLastError());
 }
 
+int g_tpw_override = 0;
+
 }  // namespace
+
+void set_rotate_tpw_override(int tpw) { g_tpw_override = tpw; }
 
 pme_status launch_rotate_mfma(const RotateArgs& a) {
     // Shapes covered: 32 <= 2^k <= 512.  bf16 input is copied to LDS in 16-byte pieces, so d, the row
@@ -488,25 +544,26 @@ pme_status launch_rotate_mfma(const RotateArgs& a) {
     const int ks = (rows + 31) / 32;
     const int nt = (a.b + 15) / 16;
     if (ks > kMaxKs || nt > kMaxTiles) return PME_ERR_UNSUPPORTED_PATH;
-    // a'-tiles per wave: bounded by registers (4 * 2^k / 16 accumulators per tile).
+    // a'-tiles per wave: bounded by registers (4 * 2^k / 16 accumulators per tile); fewer tiles per wave
+    // mean more, lighter waves per token, which measured faster from 2^k = 128 up.
     int tpw;
     switch (a.k) {
         case 5: tpw = 5; break;
         case 6: tpw = 3; break;
-        case 7: tpw = 3; break;
-        case 8: tpw = 2; break;
+        case 7: tpw = 2; break;
         default: tpw = 1; break;
     }
     // few tokens: spread a token over as many waves as it has tiles
     if (a.T < 512 && a.k <= 8) tpw = 1;
+    if (g_tpw_override > 0) tpw = g_tpw_override;
     const int nwaves = (nt + tpw - 1) / tpw;
     if (nwaves > kMaxWaves) return PME_ERR_UNSUPPORTED_PATH;
 #define PME_ROT(K, TP)                                                             \
     if (a.k == K && tpw == TP)                                                     \
         return f32 ? launch_one<K, TP, true>(a, ks, nwaves) : launch_one<K, TP, false>(a, ks, nwaves);
-    PME_ROT(5, 5) PME_ROT(5, 1)
-    PME_ROT(6, 3) PME_ROT(6, 1)
-    PME_ROT(7, 3) PME_ROT(7, 1)
+    PME_ROT(5, 5) PME_ROT(5, 3) PME_ROT(5, 1)
+    PME_ROT(6, 3) PME_ROT(6, 2) PME_ROT(6, 1)
+    PME_ROT(7, 3) PME_ROT(7, 2) PME_ROT(7, 1)
     PME_ROT(8, 2) PME_ROT(8, 1)
     PME_ROT(9, 1)
 #undef PME_ROT
