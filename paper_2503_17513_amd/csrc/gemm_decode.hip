@@ -1,0 +1,116 @@
+// W4A4 GEMM for decode shapes (at most 16 tokens): memory-bound on the packed weights.
+//
+//   acc[t][n] = sum_j qx[t][j] qw[n][j],  y[t][n] = bf16(acc * sx[t] * sw[n])   (paper Sections 3 and 4).
+//
+// One workgroup owns 16 output channels and the whole of K; its waves split K into contiguous runs of
+// 64-byte chunks (128 codes), so that every weight byte is loaded exactly once, straight from HBM into
+// registers, with all of a wave's loads in flight before the first use.  A chunk of 16 channels is one
+// global_load_dwordx4 per lane (lane = channel % 16 + 16 * quarter of the chunk) and feeds two
+// v_mfma_i32_16x16x64_i8 (even and odd codes, unpacked in registers as in the prefill kernel:
+// (w & 0x0F0F0F0F) << 4 and w & 0xF0F0F0F0, accumulator = 256 x the sum).  The tokens are the other MFMA
+// operand (rows beyond T repeat the last token and are dropped).  The waves' partial 16 x 16 tiles are
+// summed through LDS and the first four waves apply the scales and store bf16.
+#include "pme_internal.h"
+
+namespace pme {
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+
+enum { MODE_BF16 = 0, MODE_ASYM = 1, MODE_I32 = 2 };
+constexpr int kBatch = 6;      // chunks a wave keeps in flight at once
+
+template <int NW, int MODE>
+__global__ void __launch_bounds__(64 * NW)
+k_gemm_decode(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
+              const float* __restrict__ sx, const float* __restrict__ sw,
+              const int32_t* __restrict__ zx, const int32_t* __restrict__ wsum,
+              int T, int N, int kb, void* __restrict__ out, int64_t ldo) {
+    __shared__ int part[NW][64][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, kg = lane >> 4;
+    const int n0 = blockIdx.x * 16;
+    const int nchunks = kb >> 6;
+    const int c0 = (int)(((int64_t)wave * nchunks) / NW), c1 = (int)(((int64_t)(wave + 1) * nchunks) / NW);
+    const uint8_t* wrow = qw + (int64_t)min(n0 + r, N - 1) * kb + kg * 16;
+    const uint8_t* xrow = qx + (int64_t)min(r, T - 1) * kb + kg * 16;
+
+    i32x4 acc = {0, 0, 0, 0};
+    for (int c = c0; c < c1; c += kBatch) {
+        u32x4 w[kBatch], x[kBatch];
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            const int cc = min(c + i, c1 - 1);          // surplus slots repeat the last chunk and are not used
+            w[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow + (int64_t)cc * 64));
+            x[i] = *reinterpret_cast<const u32x4*>(xrow + (int64_t)cc * 64);
+        }
+#pragma unroll
+        for (int i = 0; i < kBatch; ++i) {
+            if (c + i < c1) {
+                u32x4 xv = x[i];
+                if (MODE == MODE_ASYM) xv ^= 0x88888888u;      // unsigned code u: u ^ 8 as a signed nibble is u - 8
+                i32x4 wlo, whi, xlo, xhi;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    wlo[e] = (int)((w[i][e] & 0x0F0F0F0Fu) << 4);
+                    whi[e] = (int)(w[i][e] & 0xF0F0F0F0u);
+                    xlo[e] = (int)((xv[e] & 0x0F0F0F0Fu) << 4);
+                    xhi[e] = (int)(xv[e] & 0xF0F0F0F0u);
+                }
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wlo, xlo, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(whi, xhi, acc, 0, 0, 0);
+            }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) part[wave][lane][i] = acc[i];
+    __syncthreads();
+    if (tid < 256) {
+        // element tid = 4 * lane' + i of the 16 x 16 tile: channel 4 * (lane' / 16) + i, token lane' % 16
+        const int ln = tid >> 2, i = tid & 3;
+        int s = 0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) s += part[w][ln][i];
+        s >>= 8;                                        // exact: the low 8 bits are zero
+        const int t = ln & 15, n = n0 + 4 * (ln >> 4) + i;
+        if (t < T && n < N) {
+            if (MODE == MODE_ASYM) s -= (zx[t] - 8) * wsum[n];
+            if (MODE == MODE_I32) {
+                static_cast<int32_t*>(out)[(int64_t)t * ldo + n] = s;
+            } else {
+                const float y = (float)s * sx[t] * sw[n];
+                static_cast<uint16_t*>(out)[(int64_t)t * ldo + n] = f32_to_bf16_bits(y);
+            }
+        }
+    }
+}
+
+template <int NW>
+pme_status launch_nw(const GemmArgs& a) {
+    const dim3 grid((unsigned)((a.N + 15) / 16)), block(64 * NW);
+    const int kb = (int)(a.d_e / 2);
+#define PME_LAUNCH(MODE)                                                                                   \
+    hipLaunchKernelGGL((k_gemm_decode<NW, MODE>), grid, block, 0, a.stream, a.qx, a.qw, a.sx, a.sw, a.zx, a.wsum, \
+                       (int)a.T, (int)a.N, kb, a.y, a.ldy)
+    if (a.out_i32) PME_LAUNCH(MODE_I32);
+    else if (a.zx) PME_LAUNCH(MODE_ASYM);
+    else PME_LAUNCH(MODE_BF16);
+#undef PME_LAUNCH
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace
+
+pme_status launch_gemm_decode(const GemmArgs& a) {
+    // at most 16 tokens, whole 64-byte chunks, 16-byte aligned rows
+    if (a.T > 16 || a.d_e % 128 || a.d_e > (1 << 17)) return PME_ERR_UNSUPPORTED_PATH;
+    if ((reinterpret_cast<uintptr_t>(a.qx) & 15) || (reinterpret_cast<uintptr_t>(a.qw) & 15)) return PME_ERR_UNSUPPORTED_PATH;
+    if (a.zx && a.out_i32) return PME_ERR_UNSUPPORTED_PATH;
+    const int64_t nchunks = a.d_e / 128;
+    if (nchunks >= 32) return launch_nw<16>(a);
+    if (nchunks >= 8) return launch_nw<8>(a);
+    return launch_nw<4>(a);
+}
+
+}  // namespace pme

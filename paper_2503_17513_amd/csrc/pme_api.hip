@@ -62,7 +62,7 @@ pme_status run_gemm(const pme::GemmArgs& a) {
     if (a.T == 0 || a.N == 0) return PME_OK;
     int path = g_path.load();
     if (path != PME_PATH_GENERIC) {
-        pme_status s = pme::launch_gemm_mfma(a);
+        pme_status s = (a.T <= 16) ? pme::launch_gemm_decode(a) : pme::launch_gemm_mfma(a);
         if (s != PME_ERR_UNSUPPORTED_PATH || path == PME_PATH_MFMA) return s;
     }
     return pme::launch_gemm_generic(a);

@@ -37,6 +37,7 @@ pme_status launch_rotate_generic(const RotateArgs& a);
 pme_status launch_rotate_mfma(const RotateArgs& a);
 pme_status launch_gemm_generic(const GemmArgs& a);
 pme_status launch_gemm_mfma(const GemmArgs& a);
+pme_status launch_gemm_decode(const GemmArgs& a);
 pme_status launch_weight_rowsum(const uint8_t* qw, int64_t N, int64_t d_e, int32_t* wsum, hipStream_t s);
 pme_status launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 void set_gemm_tile_override(int id);

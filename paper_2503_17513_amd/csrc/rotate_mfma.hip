@@ -228,7 +228,9 @@ __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
 // Most waves a workgroup of this instantiation is launched with (bounds the registers per lane).
 template <int KLOG2, int TPW> constexpr int max_waves() { return (TPW == 1 && KLOG2 <= 8) ? kMaxWaves : kMaxWaves / 2; }
 
-template <int KLOG2, int TPW, bool F32IN>
+enum { OUT_SYM = 0, OUT_ASYM = 1, OUT_XHAT = 2 };   // symmetric codes, asymmetric codes, fp32 rotated values
+
+template <int KLOG2, int TPW, bool F32IN, int OUT>
 __global__ void __launch_bounds__((64 * max_waves<KLOG2, TPW>()))
 k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, int b, int ks_count, int slot,
               double gamma, uint8_t* __restrict__ qx, float* __restrict__ sx, int32_t* __restrict__ zx,
@@ -245,16 +247,8 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
     const int nwaves = blockDim.x >> 6, nthreads = blockDim.x;
     const int l15 = lane & 15, g = lane >> 4;
     const int rows_k = 32 * ks_count;                 // rows of the K-padded operand
-    const int ntiles = (b + 15) >> 4;
     unsigned char* bsm = smem + NS * plane_bytes + (size_t)wave * TPW * ks_count * 1024;   // this wave's B fragments
 
-    // ---- once per workgroup: B fragments of P into LDS, zero padding of the token buffer
-#pragma unroll
-    for (int ti = 0; ti < TPW; ++ti) {
-        const int tile = min(wave * TPW + ti, kMaxTiles - 1);
-        for (int ks = 0; ks < ks_count; ++ks)
-            *reinterpret_cast<u32x4*>(bsm + ((size_t)(ti * ks_count + ks) * 64 + lane) * 16) = g_ptable[slot][tile * kMaxKs + ks][lane];
-    }
     const int real_groups = (((d + NC - 1) >> KLOG2) + 3) >> 2;        // 4-row groups holding real inputs
     const int nchunks = real_groups * MT * 8;
     if constexpr (!F32IN) {
@@ -316,7 +310,14 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
 
     int64_t t = blockIdx.x;
     if constexpr (!F32IN) {
-        if (t < T) load_token_dma(t);
+        if (t < T) load_token_dma(t);       // in flight while the B fragments are fetched
+    }
+    // ---- once per workgroup: B fragments of P into LDS
+#pragma unroll
+    for (int ti = 0; ti < TPW; ++ti) {
+        const int tile = min(wave * TPW + ti, kMaxTiles - 1);
+        for (int ks = 0; ks < ks_count; ++ks)
+            *reinterpret_cast<u32x4*>(bsm + ((size_t)(ti * ks_count + ks) * 64 + lane) * 16) = g_ptable[slot][tile * kMaxKs + ks][lane];
     }
     const int l4 = (lane >> 4) & 1, l5 = lane >> 5;
     const int c0 = run_start<KLOG2>(l4, l5);
@@ -354,9 +355,8 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
                     const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                     const bf16x8 af = __builtin_bit_cast(bf16x8, both);
 #pragma unroll
-                    for (int ti = 0; ti < TPW; ++ti)
-                        if ((wave * TPW + ti) < ntiles)
-                            acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfrag[ti], acc[ti][mt], 0, 0, 0);
+                    for (int ti = 0; ti < TPW; ++ti)   // tiles beyond the block have all-zero B fragments
+                        acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfrag[ti], acc[ti][mt], 0, 0, 0);
                 } else {
 #pragma unroll
                     for (int sp = 0; sp < NS; ++sp) {
@@ -365,8 +365,7 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
                         const bf16x8 af = __builtin_bit_cast(bf16x8, raw);
 #pragma unroll
                         for (int ti = 0; ti < TPW; ++ti)
-                            if ((wave * TPW + ti) < ntiles)
-                                acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfrag[ti], acc[ti][mt], 0, 0, 0);
+                            acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfrag[ti], acc[ti][mt], 0, 0, 0);
                     }
                 }
             }
@@ -386,10 +385,10 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
             for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
                 for (int r = 0; r < 4; ++r) v[ti][mt * 4 + r] = acc[ti][mt][r];
-            if ((wave * TPW + ti) < ntiles) fwht_lane<KLOG2>(v[ti]);
+            if ((wave * TPW + ti) * 16 < b) fwht_lane<KLOG2>(v[ti]);   // tiles beyond the block hold zeros
         }
 
-        if (xhat) {
+        if constexpr (OUT == OUT_XHAT) {
             const float gf = (float)gamma;
 #pragma unroll
             for (int ti = 0; ti < TPW; ++ti) {
@@ -401,11 +400,10 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
                 }
             }
         }
-        if (!qx) continue;
-
+        if constexpr (OUT != OUT_XHAT) {
         // ---- per-token range
         float hi = 0.f, lo = 0.f;
-        if (zx) {
+        if constexpr (OUT == OUT_ASYM) {
 #pragma unroll
             for (int ti = 0; ti < TPW; ++ti)
 #pragma unroll
@@ -433,7 +431,7 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
 
         float s = 1.f, rinv = 0.f;
         int z = 0;
-        if (!zx) {
+        if constexpr (OUT == OUT_SYM) {
             if (hi > 0.f) {
                 s = (float)((double)hi * gamma / 7.0);
                 rinv = (float)(gamma / (double)s);
@@ -458,11 +456,12 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
         constexpr uint32_t kCsum = kC * 0x11111111u;
 #pragma unroll
         for (int ti = 0; ti < TPW; ++ti) {
+            if ((wave * TPW + ti) * 16 >= b) continue;      // wave-uniform: nothing to store for this tile
             const int ap = (wave * TPW + ti) * 16 + l15;
             uint32_t words[L::RUN / 8];
 #pragma unroll
             for (int wd = 0; wd < L::RUN / 8; ++wd) {
-                if (!zx) {
+                if constexpr (OUT == OUT_SYM) {
                     uint32_t accw = 0;
 #pragma unroll
                     for (int nb = 7; nb >= 0; --nb) {
@@ -495,12 +494,13 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
                 }
             }
         }
+        }   // OUT != OUT_XHAT
     }
     wait_all_vm();
 }
 
-template <int KLOG2, int TPW, bool F32IN>
-pme_status launch_one(const RotateArgs& a, int ks, int nwaves) {
+template <int KLOG2, int TPW, bool F32IN, int OUT>
+pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     using L = Layout<KLOG2>;
     constexpr int NS = F32IN ? 3 : 1;
     const size_t lds = (size_t)NS * ks * L::MT * 1024 + (size_t)nwaves * TPW * ks * 1024;
@@ -509,7 +509,7 @@ pme_status launch_one(const RotateArgs& a, int ks, int nwaves) {
     pme_status st = PME_OK;
     const int slot = table_slot(a.b, rows, a.stream, &st);
     if (slot < 0) return st;
-    auto kern = k_rotate_mfma<KLOG2, TPW, F32IN>;
+    auto kern = k_rotate_mfma<KLOG2, TPW, F32IN, OUT>;
     if (lds > 48 * 1024) {
         if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
             return PME_ERR_HIP;
@@ -524,6 +524,13 @@ pme_status launch_one(const RotateArgs& a, int ks, int nwaves) {
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * nwaves), lds, a.stream, a.x, a.ldx, (int)a.T, (int)a.d,
                        (int)a.d_e, a.b, ks, slot, gamma, a.qx, a.sx, a.zx, a.xhat);
     return hip_status(hipGetLastError());
+}
+
+template <int KLOG2, int TPW, bool F32IN>
+pme_status launch_one(const RotateArgs& a, int ks, int nwaves) {
+    if (a.xhat) return launch_out<KLOG2, TPW, F32IN, OUT_XHAT>(a, ks, nwaves);
+    if (a.zx) return launch_out<KLOG2, TPW, F32IN, OUT_ASYM>(a, ks, nwaves);
+    return launch_out<KLOG2, TPW, F32IN, OUT_SYM>(a, ks, nwaves);
 }
 
 int g_tpw_override = 0;

@@ -127,6 +127,10 @@ GEMM_CASES = [
     ("tile_256x256", 4000, 4100, 128, (MFMA,)),
     ("single_row_col", 1, 1, 2176, (GENERIC, MFMA)),
     ("decode_shape", 8, 2048, 8448, (GENERIC, MFMA)),
+    ("decode_16_tokens_ragged_n", 16, 100, 384, (GENERIC, MFMA)),
+    ("decode_one_chunk", 3, 40, 128, (GENERIC, MFMA)),
+    ("decode_one_token_long_k", 1, 520, 15360, (GENERIC, MFMA)),
+    ("seventeen_tokens_use_the_tiled_kernel", 17, 64, 256, (GENERIC, MFMA)),
 ]
 
 
@@ -181,10 +185,11 @@ def test_gemm_every_tile_configuration(tile):
     check_bf16(y, oracle.dequant_bf16(acc_ref, sx, sw))
 
 
+@pytest.mark.parametrize("T", (150, 8))
 @pytest.mark.parametrize("path", (GENERIC, MFMA))
-def test_gemm_asymmetric(path):
+def test_gemm_asymmetric(path, T):
     rng = np.random.default_rng(8)
-    T, N, d_e = 150, 260, 384
+    N, d_e = 260, 384
     q = rng.integers(0, 16, size=(T, d_e), dtype=np.uint8)
     z = rng.integers(0, 16, size=T).astype(np.int32)
     qw = rng.integers(-8, 8, size=(N, d_e), dtype=np.int8)
