@@ -117,6 +117,18 @@ pme_status pme_expanded_linear(const void* x, pme_dtype xt, int64_t T, int64_t d
                                void* y_bf16, int64_t ldy, void* workspace, size_t workspace_bytes,
                                void* stream);
 
+/*
+ * Offline weight side (Section 3: W_hat = H_hat^T W; Section 4: per-channel symmetric int4, here by
+ * round-to-nearest): expands and quantizes a weight matrix into the qw / sw operands of pme_w4a4_gemm.
+ *   wt  DEVICE [N, d] row-major (one row of d input weights per output channel, i.e. W^T of the paper's
+ *       d x N matrix), element type wtype, ldw elements between rows.
+ *   qw  DEVICE out [N, d_e / 2] packed int4,  sw  DEVICE out [N] fp32 (scale = absmax / 7 per channel).
+ * Row n of W_hat^T is the rotation of row n of W^T, so this is the activation transform applied to the
+ * rows of wt; same alignment rules as pme_hadamard_expand_quant.  GPTQ-style calibration is not done.
+ */
+pme_status pme_expand_quantize_weights(const void* wt, pme_dtype wtype, int64_t N, int64_t d, int64_t ldw,
+                                       int64_t d_e, uint8_t* qw, float* sw, void* stream);
+
 /* Bytes of workspace pme_expanded_linear needs (0 on invalid sizes). */
 size_t pme_workspace_bytes(int64_t T, int64_t d, int64_t d_e, int64_t N);
 

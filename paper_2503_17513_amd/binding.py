@@ -14,7 +14,7 @@ PATH_AUTO, PATH_GENERIC, PATH_MFMA = 0, 1, 2
 F32, BF16 = 0, 1
 
 # Every symbol include/pme.h declares.
-EXPORTS = ("pme_hadamard_expand_quant", "pme_hadamard_expand_quant_asym", "pme_w4a4_gemm", "pme_w4a4_gemm_asym",
+EXPORTS = ("pme_hadamard_expand_quant", "pme_expand_quantize_weights", "pme_hadamard_expand_quant_asym", "pme_w4a4_gemm", "pme_w4a4_gemm_asym",
            "pme_weight_rowsum", "pme_expanded_linear", "pme_workspace_bytes", "pme_hadamard_expand_f32",
            "pme_w4a4_gemm_i32", "pme_factor_order", "pme_base_block", "pme_probe_copy", "pme_set_path", "pme_set_gemm_tile",
            "pme_get_path", "pme_status_string", "pme_version")
@@ -40,6 +40,7 @@ def lib() -> C.CDLL:
     L = C.CDLL(_LIB_PATH)
     i64, vp, sz, i32 = C.c_int64, C.c_void_p, C.c_size_t, C.c_int
     L.pme_hadamard_expand_quant.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp]
+    L.pme_expand_quantize_weights.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp]
     L.pme_hadamard_expand_quant_asym.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp, vp]
     L.pme_hadamard_expand_f32.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp]
     L.pme_w4a4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, vp]
@@ -138,6 +139,16 @@ def hadamard_expand_quant(x: torch.Tensor, d_e: int, qx: torch.Tensor | None = N
     _check(lib().pme_hadamard_expand_quant(_dev(x, "x"), _dtype_code(x), T, d, ldx, d_e, _dev(qx, "qx"),
                                            _dev(sx, "sx"), _stream()), "pme_hadamard_expand_quant")
     return qx, sx
+
+
+def expand_quantize_weights(wt: torch.Tensor, d_e: int):
+    """wt: [N, d] (torch Linear layout, W^T of the paper's d x N matrix) -> (qw [N, d_e/2], sw [N])."""
+    N, d, ldw = _rows(wt)
+    qw = torch.empty((N, d_e // 2), dtype=torch.uint8, device=wt.device)
+    sw = torch.empty((N,), dtype=torch.float32, device=wt.device)
+    _check(lib().pme_expand_quantize_weights(_dev(wt, "wt"), _dtype_code(wt), N, d, ldw, d_e, qw.data_ptr(),
+                                             sw.data_ptr(), _stream()), "pme_expand_quantize_weights")
+    return qw, sw
 
 
 def hadamard_expand_quant_asym(x: torch.Tensor, d_e: int):

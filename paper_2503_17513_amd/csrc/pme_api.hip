@@ -86,6 +86,11 @@ pme_status pme_hadamard_expand_quant(const void* x, pme_dtype xt, int64_t T, int
     return run_rotate(a);
 }
 
+pme_status pme_expand_quantize_weights(const void* wt, pme_dtype wtype, int64_t N, int64_t d, int64_t ldw,
+                                       int64_t d_e, uint8_t* qw, float* sw, void* stream) {
+    return pme_hadamard_expand_quant(wt, wtype, N, d, ldw, d_e, qw, sw, stream);
+}
+
 pme_status pme_hadamard_expand_quant_asym(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
                                           int64_t d_e, uint8_t* qx, float* sx, int32_t* zx, void* stream) {
     int b, k;

@@ -241,6 +241,29 @@ def test_expanded_linear_end_to_end(name, shape):
     assert nflip <= max(1, int(1e-4 * q_gpu.size))
 
 
+@pytest.mark.parametrize("d,d_e,N,dtype", ((64, 80, 48, "f32"), (2048, 2176, 300, "f32"), (8192, 8704, 130, "bf16")))
+def test_offline_weight_expansion_and_whole_layer_from_real_weights(d, d_e, N, dtype):
+    # W_hat = H_hat^T W then per-channel round-to-nearest int4 (Sections 3 and 4), on the GPU, against the
+    # oracle; then the whole quantized layer built from those weights tracks the unquantized X W.
+    rng = np.random.default_rng(d + N)
+    W = (rng.standard_normal((d, N)) / np.sqrt(d)).astype(np.float32)
+    if dtype == "bf16":
+        W = torch.from_numpy(W).to(torch.bfloat16).to(torch.float32).numpy()
+    What = oracle.expand_weight(W, d_e)
+    q_ref, s_ref = oracle.quantize_weight_rtn(What)
+    wt = to_device(np.ascontiguousarray(W.T), dtype)
+    qw, sw = pme.expand_quantize_weights(wt, d_e)
+    check_scales(sw.cpu().numpy(), s_ref)
+    check_codes(unpack_gpu(qw), q_ref, What.T, s_ref)
+    T = 24
+    x = _acts(T, d, d_e, dtype, seed=9)
+    y = pme.expanded_linear(to_device(x, dtype), d_e, qw, sw).to(torch.float32).cpu().numpy()
+    ref = x.astype(np.float64) @ W.astype(np.float64)
+    assert np.linalg.norm(y - ref) / np.linalg.norm(ref) < 0.25
+    y_or = oracle.expanded_linear(x, d_e, unpack_gpu(qw), sw.cpu().numpy())["y"]
+    assert np.linalg.norm(y - y_or) <= 2e-3 * np.linalg.norm(y_or)
+
+
 def test_run_twice_is_bit_identical():
     wl = make_workload(custom_spec(257, 2048, 2176, 384, seed=4))
     xd = to_device(wl.x, "bf16")
