@@ -68,6 +68,8 @@ def main() -> int:
     ap.add_argument("--workload", default="C2", help="C1..C5 (default C2, the configuration the metric is quoted on)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--stages", action="store_true", help="also time each stage and every other workload")
+    ap.add_argument("--mxfp4", action="store_true",
+                    help="also time the MXFP4 variant of the layer (the paper's second quantization setting)")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also run the library's plain 1 GiB copy kernel (the known-size dispatch that calibrates "
                          "the profiler's FETCH_SIZE / WRITE_SIZE counters)")
@@ -182,6 +184,19 @@ def main() -> int:
             del wl2, b2
             torch.cuda.empty_cache()
         out["other_workloads"] = others
+    if args.mxfp4:
+        wt = torch.randn((sp.N, sp.d), device="cuda").to(torch.bfloat16)     # any weights: timing only
+        qw4, ew4 = pme.hadamard_expand_quant_mxfp4(wt, sp.d_e)
+        qx4, ex4 = pme.hadamard_expand_quant_mxfp4(b["x"], sp.d_e)
+        for _ in range(5):
+            pme.expanded_linear_mxfp4(b["x"], sp.d_e, qw4, ew4, b["y"], b["ws"])
+        it = max(20, args.steps)
+        t_l = _event_ms(lambda: pme.expanded_linear_mxfp4(b["x"], sp.d_e, qw4, ew4, b["y"], b["ws"]), it)
+        t_r = _event_ms(lambda: pme.hadamard_expand_quant_mxfp4(b["x"], sp.d_e), it)
+        t_g = _event_ms(lambda: pme.mxfp4_gemm(qx4, ex4, qw4, ew4, b["y"]), it)
+        out["mxfp4"] = {"layer_us": t_l * 1e3, "layer_tflops": ops / (t_l * 1e-3) / 1e12, "rotate_quant_us": t_r * 1e3,
+                        "gemm_us": t_g * 1e3, "gemm_tflops": ops / (t_g * 1e-3) / 1e12, "gemm_peak_tflops": 10100.0,
+                        "gemm_frac": ops / (t_g * 1e-3) / 1e12 / 10100.0}
     if args.probe_copy:
         src = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)

@@ -129,7 +129,31 @@ pme_status pme_expanded_linear(const void* x, pme_dtype xt, int64_t T, int64_t d
 pme_status pme_expand_quantize_weights(const void* wt, pme_dtype wtype, int64_t N, int64_t d, int64_t ldw,
                                        int64_t d_e, uint8_t* qw, float* sw, void* stream);
 
-/* Bytes of workspace pme_expanded_linear needs (0 on invalid sizes). */
+/*
+ * OCP MXFP4 variants (Section 4, second setting: MXFP4 for weights and activations, one E8M0 scale per
+ * group of 32 elements).  Element format FP4 E2M1 (magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6), block scale
+ * 2^(byte - 127) with byte - 127 = floor(log2(block absmax)) - 2, elements rounded half to even and
+ * saturating at +-6, an all-zero block takes byte 0.  d_e must be a multiple of 32.
+ *   qx DEVICE out [T, d_e/2] packed E2M1 codes (even index in the low nibble),
+ *   ex DEVICE out [T, d_e/32] E8M0 bytes.
+ * Applied to the rows of a [N, d] weight matrix (W^T) the same call is the offline weight side.
+ */
+pme_status pme_hadamard_expand_quant_mxfp4(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                                           int64_t d_e, uint8_t* qx, uint8_t* ex, void* stream);
+
+/* y[t][n] = bf16(sum over blocks of 32 of 2^(ex-127) 2^(ew-127) sum_i P_x,i P_w,i), fp32 accumulation.
+ *   qx [T, d_e/2], ex [T, d_e/32], qw [N, d_e/2], ew [N, d_e/32] DEVICE; y DEVICE out [T, N] bf16, pitch ldy. */
+pme_status pme_mxfp4_gemm(const uint8_t* qx, const uint8_t* ex, const uint8_t* qw, const uint8_t* ew,
+                          int64_t T, int64_t d_e, int64_t N, void* y_bf16, int64_t ldy, void* stream);
+
+/* The whole MXFP4 expanded layer: the two calls above, codes and scale bytes passing through `workspace`
+ * (DEVICE, 256-byte aligned, at least pme_workspace_bytes bytes). */
+pme_status pme_expanded_linear_mxfp4(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                                     int64_t d_e, const uint8_t* qw, const uint8_t* ew, int64_t N,
+                                     void* y_bf16, int64_t ldy, void* workspace, size_t workspace_bytes,
+                                     void* stream);
+
+/* Bytes of workspace pme_expanded_linear and pme_expanded_linear_mxfp4 need (0 on invalid sizes). */
 size_t pme_workspace_bytes(int64_t T, int64_t d, int64_t d_e, int64_t N);
 
 /* ---- parity / debug exports ---- */
@@ -155,7 +179,8 @@ pme_status pme_base_block(int64_t b, int8_t* out_bxb);
 pme_status pme_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 
 /* Tuning hook for benchmarks: force the MFMA GEMM's tile configuration (0 = choose from the shape;
- * 1..10 = a fixed entry of the library's tile table).  Process-wide, not thread-safe. */
+ * 1..18 = a fixed entry of the int4 kernel's tile table, 100 + (1..9) = of the MXFP4 kernel's; 0 resets
+ * both).  Process-wide, not thread-safe. */
 void pme_set_gemm_tile(int id);
 
 void pme_set_path(pme_path p);

@@ -14,7 +14,8 @@ PATH_AUTO, PATH_GENERIC, PATH_MFMA = 0, 1, 2
 F32, BF16 = 0, 1
 
 # Every symbol include/pme.h declares.
-EXPORTS = ("pme_hadamard_expand_quant", "pme_expand_quantize_weights", "pme_hadamard_expand_quant_asym", "pme_w4a4_gemm", "pme_w4a4_gemm_asym",
+EXPORTS = ("pme_hadamard_expand_quant", "pme_expand_quantize_weights", "pme_hadamard_expand_quant_mxfp4",
+           "pme_mxfp4_gemm", "pme_expanded_linear_mxfp4", "pme_hadamard_expand_quant_asym", "pme_w4a4_gemm", "pme_w4a4_gemm_asym",
            "pme_weight_rowsum", "pme_expanded_linear", "pme_workspace_bytes", "pme_hadamard_expand_f32",
            "pme_w4a4_gemm_i32", "pme_factor_order", "pme_base_block", "pme_probe_copy", "pme_set_path", "pme_set_gemm_tile",
            "pme_get_path", "pme_status_string", "pme_version")
@@ -41,6 +42,9 @@ def lib() -> C.CDLL:
     i64, vp, sz, i32 = C.c_int64, C.c_void_p, C.c_size_t, C.c_int
     L.pme_hadamard_expand_quant.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp]
     L.pme_expand_quantize_weights.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp]
+    L.pme_hadamard_expand_quant_mxfp4.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp]
+    L.pme_mxfp4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, vp]
+    L.pme_expanded_linear_mxfp4.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i64, vp, i64, vp, sz, vp]
     L.pme_hadamard_expand_quant_asym.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp, vp]
     L.pme_hadamard_expand_f32.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp]
     L.pme_w4a4_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, vp, i64, vp]
@@ -149,6 +153,42 @@ def expand_quantize_weights(wt: torch.Tensor, d_e: int):
     _check(lib().pme_expand_quantize_weights(_dev(wt, "wt"), _dtype_code(wt), N, d, ldw, d_e, qw.data_ptr(),
                                              sw.data_ptr(), _stream()), "pme_expand_quantize_weights")
     return qw, sw
+
+
+def hadamard_expand_quant_mxfp4(x: torch.Tensor, d_e: int):
+    """-> (packed E2M1 codes [T, d_e/2] uint8, E8M0 scale bytes [T, d_e/32] uint8)."""
+    T, d, ldx = _rows(x)
+    qx = torch.empty((T, d_e // 2), dtype=torch.uint8, device=x.device)
+    ex = torch.empty((T, d_e // 32), dtype=torch.uint8, device=x.device)
+    _check(lib().pme_hadamard_expand_quant_mxfp4(_dev(x, "x"), _dtype_code(x), T, d, ldx, d_e, qx.data_ptr(),
+                                                 ex.data_ptr(), _stream()), "pme_hadamard_expand_quant_mxfp4")
+    return qx, ex
+
+
+def mxfp4_gemm(qx, ex, qw, ew, y: torch.Tensor | None = None) -> torch.Tensor:
+    T, d_e, N = _gemm_shapes(qx, qw)
+    if y is None:
+        y = torch.empty((T, N), dtype=torch.bfloat16, device=qx.device)
+    _check(lib().pme_mxfp4_gemm(_dev(qx, "qx"), _dev(ex, "ex"), _dev(qw, "qw"), _dev(ew, "ew"), T, d_e, N,
+                                _dev(y, "y"), y.stride(0) if T > 1 else max(y.stride(0), N), _stream()),
+           "pme_mxfp4_gemm")
+    return y
+
+
+def expanded_linear_mxfp4(x, d_e: int, qw, ew, y: torch.Tensor | None = None, workspace: torch.Tensor | None = None):
+    T, d, ldx = _rows(x)
+    N = qw.shape[0]
+    need = workspace_bytes(T, d, d_e, N)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
+    if y is None:
+        y = torch.empty((T, N), dtype=torch.bfloat16, device=x.device)
+    _check(lib().pme_expanded_linear_mxfp4(_dev(x, "x"), _dtype_code(x), T, d, ldx, d_e, _dev(qw, "qw"),
+                                           _dev(ew, "ew"), N, _dev(y, "y"),
+                                           y.stride(0) if T > 1 else max(y.stride(0), N), _dev(workspace, "workspace"),
+                                           workspace.numel() * workspace.element_size(), _stream()),
+           "pme_expanded_linear_mxfp4")
+    return y
 
 
 def hadamard_expand_quant_asym(x: torch.Tensor, d_e: int):

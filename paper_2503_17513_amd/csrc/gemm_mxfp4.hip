@@ -1,0 +1,317 @@
+// MXFP4 x MXFP4 GEMM (the paper's second quantization setting, Section 4: OCP MXFP4 for weights and
+// activations, one E8M0 scale per 32 elements) on the block-scaled FP4 matrix instruction of gfx950:
+//
+//   y[t][n] = bf16( sum over blocks of 32 of 2^(ex - 127) 2^(ew - 127) sum_i P_x,i P_w,i ).
+//
+// v_mfma_scale_f32_32x32x64_f8f6f4 takes 32 E2M1 codes per lane (one MX block: 16 bytes, exactly what
+// one ds_read_b128 brings) and one E8M0 byte per lane for each operand, so nothing is unpacked: packed
+// codes and scale bytes travel HBM -> LDS by DMA (same staged ring as the int4 kernel) and LDS -> MFMA.
+// Accumulation is fp32 in the matrix core; the epilogue rounds to bf16 and stores 16-byte row pieces.
+#include "pme_internal.h"
+
+namespace pme {
+namespace {
+
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
+typedef __attribute__((ext_vector_type(2))) float f32x2;
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
+
+#define PME_AS3 __attribute__((address_space(3)))
+
+template <int RB> __device__ __forceinline__ int swz(int r) {
+    return RB == 64 ? (((r >> 1) ^ (r >> 3)) & 3) : ((r >> 1) & 7);
+}
+__device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
+template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
+// DMA of 16 / 4 bytes per lane into LDS at lds_base + 16 / 4 * lane (lds_base wave-uniform).  Overwrites M0,
+// which the compiler does not keep values in; nothing else in this kernel makes the compiler use M0.
+__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ void dma4(const void* gptr, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
+    const bf16x2 p = __builtin_convertvector(f32x2{a, b}, bf16x2);
+    return __builtin_bit_cast(uint32_t, p);
+}
+
+// BM x BN output tile, WGM x WGN waves, RB packed bytes (2 RB codes, RB / 16 scale bytes) per row and K step.
+template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE>
+__global__ void __launch_bounds__(64 * WGM * WGN)
+k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, const uint8_t* __restrict__ qw,
+              const uint8_t* __restrict__ ew, int T, int N, int kb, int eb, uint16_t* __restrict__ y, int64_t ldo,
+              int tiles_m, int tiles_n, int vec_store) {
+    constexpr int NW = WGM * WGN;
+    constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
+    constexpr int ROWS = BM + BN;
+    constexpr int CPR = RB / 16, RPB = 64 / CPR, BLKS = ROWS / RPB;
+    constexpr int CH = (BLKS + NW - 1) / NW;          // code DMA instructions per wave per stage
+    constexpr int SW = RB / 64;                       // scale dwords per row per K step
+    constexpr int SBLKS = (ROWS / 64) * SW;           // scale DMA blocks (64 rows x 4 bytes) per stage
+    constexpr int SCH = (SBLKS + NW - 1) / NW;        // scale DMA instructions per wave per stage
+    constexpr int CODE_BYTES = ROWS * RB;
+    constexpr int STAGE = CODE_BYTES + ROWS * 4 * SW;
+    constexpr int NSUB = RB / 32;                     // MFMA K steps (64 codes) per K step
+    constexpr int SLAB = 32 * WN * 2;
+    static_assert(ROWS % 64 == 0, "scale DMA moves 64 rows at a time");
+    static_assert(NW * SLAB <= NSTAGE * STAGE, "epilogue staging must fit in the K-loop stages");
+
+    extern __shared__ __align__(1024) unsigned char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / WGN, wn = wave % WGN;
+    int tile = blockIdx.x;
+    const int ntiles = tiles_m * tiles_n;
+    if ((ntiles & 7) == 0) tile = (blockIdx.x & 7) * (ntiles >> 3) + (blockIdx.x >> 3);   // contiguous tiles per XCD
+    const int tm = tile / tiles_n, tn = tile % tiles_n;
+    const int m0 = tm * BM, n0 = tn * BN;
+
+    const uint8_t* src[CH];
+#pragma unroll
+    for (int s = 0; s < CH; ++s) {
+        const int r = RPB * ((wave + NW * s) % BLKS) + lane / CPR;
+        const int kc = (lane % CPR) ^ swz<RB>(r);
+        const uint8_t* base = (r < BM) ? qx + (int64_t)min(m0 + r, T - 1) * kb : qw + (int64_t)min(n0 + r - BM, N - 1) * kb;
+        src[s] = base + kc * 16;
+    }
+    // scale bytes: block sb = plane * (ROWS / 64) + rows-of-64 index; lane = row within the 64
+    const uint8_t* ssrc[SCH];
+#pragma unroll
+    for (int s = 0; s < SCH; ++s) {
+        const int sb = (wave + NW * s) % SBLKS;
+        const int plane = sb / (ROWS / 64), r = 64 * (sb % (ROWS / 64)) + lane;
+        const uint8_t* base = (r < BM) ? ex + (int64_t)min(m0 + r, T - 1) * eb : ew + (int64_t)min(n0 + r - BM, N - 1) * eb;
+        ssrc[s] = base + 4 * plane;
+    }
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(PME_AS3 unsigned char*)smem;
+    auto issue = [&](int stage, int kt) {
+#pragma unroll
+        for (int s = 0; s < CH; ++s)
+            dma16(src[s] + (int64_t)kt * RB,
+                  __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + ((wave + NW * s) % BLKS) * 1024));
+#pragma unroll
+        for (int s = 0; s < SCH; ++s)
+            dma4(ssrc[s] + (int64_t)kt * (RB / 16),
+                 __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + CODE_BYTES + ((wave + NW * s) % SBLKS) * 256));
+    };
+
+    f32x16 acc[FM][FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i)
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+    const int frow = lane & 31, fk = lane >> 5;
+    int aoff[FM], boff[FN], asoff[FM], bsoff[FN];
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+        const int r = wm * WM + 32 * i + frow;
+        aoff[i] = r * RB + ((fk ^ swz<RB>(r)) << 4);
+        asoff[i] = CODE_BYTES + r * 4;
+    }
+#pragma unroll
+    for (int j = 0; j < FN; ++j) {
+        const int r = BM + wn * WN + 32 * j + frow;
+        boff[j] = r * RB + ((fk ^ swz<RB>(r)) << 4);
+        bsoff[j] = CODE_BYTES + r * 4;
+    }
+    struct Frags { u32x4 a[FM], b[FN]; uint32_t sa[FM], sb[FN]; };
+    // sub-step s: codes of block 2 s + fk of the row (chunk position (2 s + fk) ^ swz), and its scale: byte
+    // (2 s + fk) & 3 of scale dword (2 s + fk) >> 2 = s >> 1, moved to byte 0
+    auto load_frags = [&](Frags& f, const unsigned char* stage, int s) {
+        const int sh = 16 * (s & 1) + 8 * fk;
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            f.a[i] = *reinterpret_cast<const u32x4*>(stage + (aoff[i] ^ (s << 5)));
+            f.sa[i] = *reinterpret_cast<const uint32_t*>(stage + asoff[i] + (s >> 1) * ROWS * 4) >> sh;
+        }
+#pragma unroll
+        for (int j = 0; j < FN; ++j) {
+            f.b[j] = *reinterpret_cast<const u32x4*>(stage + (boff[j] ^ (s << 5)));
+            f.sb[j] = *reinterpret_cast<const uint32_t*>(stage + bsoff[j] + (s >> 1) * ROWS * 4) >> sh;
+        }
+    };
+    auto mfma_all = [&](const Frags& f) {
+#pragma unroll
+        for (int i = 0; i < FM; ++i) {
+            const i32x8 xa = {(int)f.a[i][0], (int)f.a[i][1], (int)f.a[i][2], (int)f.a[i][3], 0, 0, 0, 0};
+#pragma unroll
+            for (int j = 0; j < FN; ++j) {
+                const i32x8 wb = {(int)f.b[j][0], (int)f.b[j][1], (int)f.b[j][2], (int)f.b[j][3], 0, 0, 0, 0};
+                // formats 4 = FP4 E2M1 for both operands; scale byte 0 of each lane's scale register
+                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wb, xa, acc[i][j], 4, 4, 0, (int)f.sb[j], 0,
+                                                                            (int)f.sa[i]);
+            }
+        }
+    };
+
+    // Pipeline over sub-steps g = kt NSUB + s: read the fragments of g + 1 while the matrix cores work on g.
+    // Before the region whose read first touches K step kt + 1 (s = NSUB - 1) every read of K step kt has been
+    // issued: wait for the DMA of kt + 1, barrier, start the DMA of kt + NSTAGE into the stage just left.
+    const int KT = kb / RB;
+#pragma unroll
+    for (int st = 0; st < NSTAGE; ++st) issue(st, min(st, KT - 1));
+    wait_vm<(NSTAGE - 1) * (CH + SCH)>();
+    lds_barrier();
+    Frags raw[2];
+    load_frags(raw[0], smem, 0);
+    int cur = 0;
+    for (int kt = 0; kt + 1 < KT; ++kt) {
+        const int nxt = (cur == NSTAGE - 1) ? 0 : cur + 1;
+        const unsigned char* scur = smem + cur * STAGE;
+        const unsigned char* snxt = smem + nxt * STAGE;
+#pragma unroll
+        for (int s = 0; s < NSUB; ++s) {
+            if (s == NSUB - 1) {
+                wait_vm<(NSTAGE - 2) * (CH + SCH)>();
+                lds_barrier();
+                issue(cur, min(kt + NSTAGE, KT - 1));
+                load_frags(raw[(s + 1) & 1], snxt, 0);
+            } else {
+                load_frags(raw[(s + 1) & 1], scur, s + 1);
+            }
+            mfma_all(raw[s & 1]);
+        }
+        cur = nxt;
+    }
+    {
+        const unsigned char* scur = smem + cur * STAGE;
+#pragma unroll
+        for (int s = 0; s < NSUB; ++s) {
+            if (s + 1 < NSUB) load_frags(raw[(s + 1) & 1], scur, s + 1);
+            mfma_all(raw[s & 1]);
+        }
+    }
+    wait_vm<0>();
+    lds_barrier();
+
+    // ---- epilogue.  Accumulator element e of block (i, j): output channel n0 + wn WN + 32 j + 8 (e / 4) + 4 fk + e % 4,
+    // token m0 + wm WM + 32 i + frow.  One 32-token slab at a time goes through LDS (private to the wave).
+    unsigned char* slab = smem + (size_t)wave * SLAB;
+#pragma unroll
+    for (int i = 0; i < FM; ++i) {
+#pragma unroll
+        for (int j = 0; j < FN; ++j)
+#pragma unroll
+            for (int eg = 0; eg < 4; ++eg) {
+                const u32x2 pk = u32x2{pack_bf16(acc[i][j][4 * eg], acc[i][j][4 * eg + 1]),
+                                       pack_bf16(acc[i][j][4 * eg + 2], acc[i][j][4 * eg + 3])};
+                *reinterpret_cast<u32x2*>(slab + frow * (WN * 2) + (32 * j + 8 * eg + 4 * fk) * 2) = pk;
+            }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        const int tbase = m0 + wm * WM + 32 * i, nbase = n0 + wn * WN;
+        if (vec_store) {
+            constexpr int CPS = WN / 8;
+#pragma unroll
+            for (int c = lane; c < 32 * CPS; c += 64) {
+                const int row = c / CPS, col = (c % CPS) * 8;
+                const u32x4 v = *reinterpret_cast<const u32x4*>(slab + row * (WN * 2) + col * 2);
+                if (tbase + row < T && nbase + col < N)
+                    *reinterpret_cast<u32x4*>(y + (int64_t)(tbase + row) * ldo + nbase + col) = v;
+            }
+        } else {
+            for (int c = lane; c < 32 * WN; c += 64) {
+                const int row = c / WN, col = c % WN;
+                if (tbase + row < T && nbase + col < N)
+                    y[(int64_t)(tbase + row) * ldo + nbase + col] = *reinterpret_cast<const uint16_t*>(slab + row * (WN * 2) + col * 2);
+            }
+        }
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    }
+}
+
+template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE>
+pme_status launch_tile(const MxGemmArgs& a) {
+    const int kb = (int)(a.d_e / 2), eb = (int)(a.d_e / 32);
+    if (kb % RB) return PME_ERR_UNSUPPORTED_PATH;
+    const int tiles_m = (int)((a.T + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
+    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WGM * WGN);
+    const size_t lds = (size_t)NSTAGE * ((BM + BN) * RB + (BM + BN) * 4 * (RB / 64));
+    auto kern = k_mxgemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE>;
+    if (lds > 64 * 1024 &&
+        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
+        return PME_ERR_HIP;
+    const int vec = (a.N % 8 == 0 && a.ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0) ? 1 : 0;
+    hipLaunchKernelGGL(kern, grid, block, lds, a.stream, a.qx, a.ex, a.qw, a.ew, (int)a.T, (int)a.N, kb, eb,
+                       static_cast<uint16_t*>(a.y), a.ldy, tiles_m, tiles_n, vec);
+    return hip_status(hipGetLastError());
+}
+
+// Plain-ALU MXFP4 GEMM, one thread per output: every shape, and the cross-check of the MFMA kernel.
+__device__ __forceinline__ float e2m1_value(uint32_t c) {
+    const uint32_t E = (c >> 1) & 3u, M = c & 1u;
+    const float mag = E == 0 ? 0.5f * (float)M : (1.f + 0.5f * (float)M) * (float)(1u << (E - 1));
+    return (c & 8u) ? -mag : mag;
+}
+__global__ void __launch_bounds__(256)
+k_mxgemm_generic(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, const uint8_t* __restrict__ qw,
+                 const uint8_t* __restrict__ ew, int T, int N, int d_e, uint16_t* __restrict__ y, int64_t ldo) {
+    const int n = blockIdx.x * 16 + (threadIdx.x & 15);
+    const int t = blockIdx.y * 16 + (threadIdx.x >> 4);
+    if (n >= N || t >= T) return;
+    const uint8_t* ar = qx + (int64_t)t * (d_e / 2);
+    const uint8_t* wr = qw + (int64_t)n * (d_e / 2);
+    double sum = 0.0;
+    for (int blk = 0; blk < d_e / 32; ++blk) {
+        float inner = 0.f;      // exact: multiples of 1/4 bounded by 32 * 36
+        for (int p = 0; p < 16; ++p) {
+            const uint32_t av = ar[blk * 16 + p], wv = wr[blk * 16 + p];
+            inner += e2m1_value(av & 0xF) * e2m1_value(wv & 0xF) + e2m1_value(av >> 4) * e2m1_value(wv >> 4);
+        }
+        const int e = (int)ex[(int64_t)t * (d_e / 32) + blk] + (int)ew[(int64_t)n * (d_e / 32) + blk] - 254;
+        sum += ldexp((double)inner, e);
+    }
+    y[(int64_t)t * ldo + n] = f32_to_bf16_bits((float)sum);
+}
+
+int g_mx_tile_override = 0;
+
+}  // namespace
+
+void set_mxgemm_tile_override(int id) { g_mx_tile_override = id; }
+
+pme_status launch_mxgemm_generic(const MxGemmArgs& a) {
+    if ((a.T + 15) / 16 > 65535) return PME_ERR_UNSUPPORTED_PATH;
+    dim3 grid((unsigned)((a.N + 15) / 16), (unsigned)((a.T + 15) / 16));
+    hipLaunchKernelGGL(k_mxgemm_generic, grid, dim3(256), 0, a.stream, a.qx, a.ex, a.qw, a.ew, (int)a.T, (int)a.N,
+                       (int)a.d_e, static_cast<uint16_t*>(a.y), a.ldy);
+    return hip_status(hipGetLastError());
+}
+
+pme_status launch_mxgemm_mfma(const MxGemmArgs& a) {
+    // whole 64-byte K steps (d_e % 128 == 0: also makes the scale rows 4-byte aligned), 16-byte aligned code rows
+    if (a.d_e % 128 || a.d_e > (1 << 20)) return PME_ERR_UNSUPPORTED_PATH;
+    if ((reinterpret_cast<uintptr_t>(a.qx) & 15) || (reinterpret_cast<uintptr_t>(a.qw) & 15) ||
+        (reinterpret_cast<uintptr_t>(a.ex) & 3) || (reinterpret_cast<uintptr_t>(a.ew) & 3))
+        return PME_ERR_UNSUPPORTED_PATH;
+    const int64_t cus = 256;
+    auto tiles = [&](int bm, int bn) { return ((a.T + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
+    int id = g_mx_tile_override;
+    if (id == 0) {
+        const bool wide = (a.d_e % 256) == 0;
+        if (tiles(256, 256) >= cus) id = wide ? 8 : 2;
+        else if (tiles(128, 192) >= cus && tiles(128, 256) < cus) id = wide ? 6 : 5;
+        else if (tiles(128, 128) >= cus) id = wide ? 3 : 4;
+        else id = 7;
+    }
+    switch (id) {
+        case 1: return launch_tile<256, 256, 2, 2, 128, 2>(a);
+        case 2: return launch_tile<256, 256, 2, 2, 64, 3>(a);
+        case 3: return launch_tile<128, 128, 2, 2, 128, 3>(a);
+        case 4: return launch_tile<128, 128, 2, 2, 64, 3>(a);
+        case 5: return launch_tile<128, 192, 2, 2, 64, 3>(a);
+        case 6: return launch_tile<128, 192, 2, 2, 128, 3>(a);
+        case 7: return launch_tile<64, 64, 2, 2, 64, 3>(a);
+        case 8: return launch_tile<256, 256, 2, 4, 128, 2>(a);
+        case 9: return launch_tile<256, 128, 2, 2, 128, 3>(a);
+    }
+    return PME_ERR_UNSUPPORTED_PATH;
+}
+
+}  // namespace pme

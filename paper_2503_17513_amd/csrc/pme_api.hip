@@ -2,6 +2,7 @@
 // arguments have been accepted.
 #include "pme_internal.h"
 
+#include <algorithm>
 #include <atomic>
 
 namespace {
@@ -82,7 +83,7 @@ pme_status pme_hadamard_expand_quant(const void* x, pme_dtype xt, int64_t T, int
     if (s != PME_OK) return s;
     if (T > 0 && (!qx || !sx)) return PME_ERR_NULL;
     if (!aligned(qx, 4) || !aligned(sx, 4)) return PME_ERR_ALIGN;
-    pme::RotateArgs a{x, xt, T, d, ldx, d_e, b, k, qx, sx, nullptr, nullptr, (hipStream_t)stream};
+    pme::RotateArgs a{x, xt, T, d, ldx, d_e, b, k, qx, sx, nullptr, nullptr, nullptr, (hipStream_t)stream};
     return run_rotate(a);
 }
 
@@ -98,7 +99,7 @@ pme_status pme_hadamard_expand_quant_asym(const void* x, pme_dtype xt, int64_t T
     if (s != PME_OK) return s;
     if (T > 0 && (!qx || !sx || !zx)) return PME_ERR_NULL;
     if (!aligned(qx, 4) || !aligned(sx, 4) || !aligned(zx, 4)) return PME_ERR_ALIGN;
-    pme::RotateArgs a{x, xt, T, d, ldx, d_e, b, k, qx, sx, zx, nullptr, (hipStream_t)stream};
+    pme::RotateArgs a{x, xt, T, d, ldx, d_e, b, k, qx, sx, zx, nullptr, nullptr, (hipStream_t)stream};
     return run_rotate(a);
 }
 
@@ -109,7 +110,7 @@ pme_status pme_hadamard_expand_f32(const void* x, pme_dtype xt, int64_t T, int64
     if (s != PME_OK) return s;
     if (T > 0 && !xhat) return PME_ERR_NULL;
     if (!aligned(xhat, 4)) return PME_ERR_ALIGN;
-    pme::RotateArgs a{x, xt, T, d, ldx, d_e, b, k, nullptr, nullptr, nullptr, xhat, (hipStream_t)stream};
+    pme::RotateArgs a{x, xt, T, d, ldx, d_e, b, k, nullptr, nullptr, nullptr, nullptr, xhat, (hipStream_t)stream};
     return run_rotate(a);
 }
 
@@ -158,8 +159,9 @@ pme_status pme_weight_rowsum(const uint8_t* qw, int64_t N, int64_t d_e, int32_t*
 size_t pme_workspace_bytes(int64_t T, int64_t d, int64_t d_e, int64_t N) {
     (void)N;
     if (T < 0 || d <= 0 || d_e <= 0 || d > d_e || (d_e & 1)) return 0;
-    // packed codes [T, d_e/2] then scales [T], each region 256-byte aligned
-    return round_up((size_t)T * (size_t)(d_e / 2), 256) + round_up((size_t)T * sizeof(float), 256);
+    // packed codes [T, d_e/2], then per-token scales [T] fp32 or MXFP4 scale bytes [T, d_e/32]; 256-byte aligned
+    const size_t scales = std::max((size_t)T * sizeof(float), (size_t)T * (size_t)(d_e / 32));
+    return round_up((size_t)T * (size_t)(d_e / 2), 256) + round_up(scales, 256);
 }
 
 pme_status pme_expanded_linear(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
@@ -179,11 +181,67 @@ pme_status pme_expanded_linear(const void* x, pme_dtype xt, int64_t T, int64_t d
     if (T == 0 || N == 0) return PME_OK;
     uint8_t* qx = static_cast<uint8_t*>(workspace);
     float* sx = reinterpret_cast<float*>(qx + round_up((size_t)T * (size_t)(d_e / 2), 256));
-    pme::RotateArgs ra{x, xt, T, d, ldx, d_e, b, k, qx, sx, nullptr, nullptr, (hipStream_t)stream};
+    pme::RotateArgs ra{x, xt, T, d, ldx, d_e, b, k, qx, sx, nullptr, nullptr, nullptr, (hipStream_t)stream};
     s = run_rotate(ra);
     if (s != PME_OK) return s;
     pme::GemmArgs ga{qx, qw, sx, sw, nullptr, nullptr, T, d_e, N, y_bf16, ldy, false, (hipStream_t)stream};
     return run_gemm(ga);
+}
+
+pme_status pme_hadamard_expand_quant_mxfp4(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                                           int64_t d_e, uint8_t* qx, uint8_t* ex, void* stream) {
+    int b, k;
+    pme_status s = check_rotate(x, xt, T, d, ldx, d_e, &b, &k);
+    if (s != PME_OK) return s;
+    if (d_e % 32) return PME_ERR_SHAPE;
+    if (T > 0 && (!qx || !ex)) return PME_ERR_NULL;
+    if (!aligned(qx, 4)) return PME_ERR_ALIGN;
+    pme::RotateArgs a{x, xt, T, d, ldx, d_e, b, k, qx, nullptr, nullptr, ex, nullptr, (hipStream_t)stream};
+    return run_rotate(a);
+}
+
+static pme_status run_mxgemm(const pme::MxGemmArgs& a) {
+    if (a.T == 0 || a.N == 0) return PME_OK;
+    int path = g_path.load();
+    if (path != PME_PATH_GENERIC) {
+        pme_status s = pme::launch_mxgemm_mfma(a);
+        if (s != PME_ERR_UNSUPPORTED_PATH || path == PME_PATH_MFMA) return s;
+    }
+    return pme::launch_mxgemm_generic(a);
+}
+
+pme_status pme_mxfp4_gemm(const uint8_t* qx, const uint8_t* ex, const uint8_t* qw, const uint8_t* ew,
+                          int64_t T, int64_t d_e, int64_t N, void* y_bf16, int64_t ldy, void* stream) {
+    if (T < 0 || N < 0 || d_e <= 0 || (d_e % 32) || ldy < N) return PME_ERR_SHAPE;
+    if (T > 0x7FFFFFFF || N > 0x7FFFFFFF || d_e > (int64_t(1) << 20)) return PME_ERR_SHAPE;
+    if (T > 0 && N > 0 && (!qx || !ex || !qw || !ew || !y_bf16)) return PME_ERR_NULL;
+    if (!aligned(qx, 4) || !aligned(qw, 4) || !aligned(y_bf16, 2)) return PME_ERR_ALIGN;
+    pme::MxGemmArgs a{qx, ex, qw, ew, T, d_e, N, y_bf16, ldy, (hipStream_t)stream};
+    return run_mxgemm(a);
+}
+
+pme_status pme_expanded_linear_mxfp4(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                                     int64_t d_e, const uint8_t* qw, const uint8_t* ew, int64_t N,
+                                     void* y_bf16, int64_t ldy, void* workspace, size_t workspace_bytes,
+                                     void* stream) {
+    int b, k;
+    pme_status s = check_rotate(x, xt, T, d, ldx, d_e, &b, &k);
+    if (s != PME_OK) return s;
+    if ((d_e % 32) || N < 0 || N > 0x7FFFFFFF || ldy < N) return PME_ERR_SHAPE;
+    if (T > 0 && N > 0 && (!qw || !ew || !y_bf16)) return PME_ERR_NULL;
+    if (!aligned(qw, 4) || !aligned(y_bf16, 2)) return PME_ERR_ALIGN;
+    const size_t need = pme_workspace_bytes(T, d, d_e, N);
+    if (T > 0 && !workspace) return PME_ERR_NULL;
+    if (!aligned(workspace, 256)) return PME_ERR_ALIGN;
+    if (workspace_bytes < need) return PME_ERR_WORKSPACE;
+    if (T == 0 || N == 0) return PME_OK;
+    uint8_t* qx = static_cast<uint8_t*>(workspace);
+    uint8_t* ex = qx + round_up((size_t)T * (size_t)(d_e / 2), 256);
+    pme::RotateArgs ra{x, xt, T, d, ldx, d_e, b, k, qx, nullptr, nullptr, ex, nullptr, (hipStream_t)stream};
+    s = run_rotate(ra);
+    if (s != PME_OK) return s;
+    pme::MxGemmArgs ga{qx, ex, qw, ew, T, d_e, N, y_bf16, ldy, (hipStream_t)stream};
+    return run_mxgemm(ga);
 }
 
 pme_status pme_factor_order(int64_t d_e, int32_t* b, int32_t* k) {
@@ -227,7 +285,11 @@ pme_status pme_probe_copy(const void* src, void* dst, size_t bytes, void* stream
     return pme::launch_probe_copy(src, dst, bytes, (hipStream_t)stream);
 }
 
-void pme_set_gemm_tile(int id) { pme::set_gemm_tile_override(id); }
+void pme_set_gemm_tile(int id) {
+    if (id >= 100) { pme::set_mxgemm_tile_override(id - 100); return; }
+    pme::set_gemm_tile_override(id);
+    if (id == 0) pme::set_mxgemm_tile_override(0);
+}
 void pme_set_path(pme_path p) { g_path.store((int)p); }
 pme_path pme_get_path(void) { return (pme_path)g_path.load(); }
 

@@ -14,9 +14,23 @@ struct RotateArgs {
     uint8_t* qx;         // packed codes out (may be null when only xhat is wanted)
     float* sx;           // scales out
     int32_t* zx;         // zero points out (asymmetric quantizer) or null
+    uint8_t* ex;         // MXFP4: E8M0 scale bytes out [T, d_e / 32] (then qx holds E2M1 codes, sx is unused)
     float* xhat;         // fp32 rotated activations out (debug) or null
     hipStream_t stream;
 };
+
+struct MxGemmArgs {
+    const uint8_t* qx;   // [T, d_e / 2] packed E2M1
+    const uint8_t* ex;   // [T, d_e / 32] E8M0
+    const uint8_t* qw;   // [N, d_e / 2]
+    const uint8_t* ew;   // [N, d_e / 32]
+    int64_t T, d_e, N;
+    void* y;             // bf16 [T, ldy]
+    int64_t ldy;
+    hipStream_t stream;
+};
+pme_status launch_mxgemm_generic(const MxGemmArgs& a);
+pme_status launch_mxgemm_mfma(const MxGemmArgs& a);
 
 struct GemmArgs {
     const uint8_t* qx;
@@ -42,6 +56,7 @@ pme_status launch_weight_rowsum(const uint8_t* qw, int64_t N, int64_t d_e, int32
 pme_status launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
 void set_gemm_tile_override(int id);
 void set_rotate_tpw_override(int tpw);
+void set_mxgemm_tile_override(int id);
 
 inline pme_status hip_status(hipError_t e) { return e == hipSuccess ? PME_OK : PME_ERR_HIP; }
 
@@ -51,6 +66,28 @@ __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
     if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((u >> 16) | 0x40u);
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
+}
+
+// E8M0 byte and power-of-two scale of an MXFP4 block whose largest magnitude is amax (>= 0, finite):
+// shared exponent floor(log2 amax) - 2 (2 = largest exponent of E2M1), byte = exponent + 127 clamped at 0.
+__device__ __forceinline__ uint32_t mx_scale_byte(float amax) {
+    const int e = (int)((__float_as_uint(amax) >> 23) & 0xFFu);   // biased exponent; 0 for zero / subnormal
+    return (uint32_t)max(e - 2, 0);
+}
+__device__ __forceinline__ float mx_scale_value(uint32_t byte) {
+    return __uint_as_float(byte ? (byte << 23) : 0x00400000u);    // 2^(byte - 127)
+}
+
+// Eight values divided by the power-of-two scale X and converted to E2M1 (round half to even, saturating),
+// packed in one dword, first value in the lowest nibble.
+__device__ __forceinline__ uint32_t mx_pack8(float f0, float f1, float f2, float f3, float f4, float f5, float f6,
+                                             float f7, float X) {
+    uint32_t w = 0;
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, f0, f1, X, 0);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, f2, f3, X, 1);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, f4, f5, X, 2);
+    w = __builtin_amdgcn_cvt_scalef32_pk_fp4_f32(w, f6, f7, X, 3);
+    return w;
 }
 
 // Entry P[a][ap] of the Paley type-I block I + [[0, 1^T], [-1, Q]], Q[i][j] = chi((i - j) mod q),

@@ -37,7 +37,7 @@ template <typename InT>
 __global__ void __launch_bounds__(kThreads)
 k_rotate_generic(const InT* __restrict__ x, int64_t ldx, int d, int d_e, int b, int k,
                  double gamma, uint8_t* __restrict__ qx, float* __restrict__ sx,
-                 int32_t* __restrict__ zx, float* __restrict__ xhat) {
+                 int32_t* __restrict__ zx, uint8_t* __restrict__ ex, float* __restrict__ xhat) {
     extern __shared__ __align__(16) float smem[];
     float* buf = smem;                                            // d_e floats
     float* red = smem + d_e;                                      // 8 floats
@@ -87,6 +87,26 @@ k_rotate_generic(const InT* __restrict__ x, int64_t ldx, int d, int d_e, int b, 
         for (int idx = tid; idx < d_e; idx += kThreads) xhat[t * d_e + idx] = buf[idx] * g;
     }
     if (!qx) return;
+
+    if (ex) {
+        // MXFP4 (OCP MX: E8M0 scale per 32 elements, E2M1 elements, round half to even, saturating)
+        const float g = (float)gamma;
+        for (int blk = tid; blk < d_e / 32; blk += kThreads) {
+            float amax = 0.f;
+            for (int i = 0; i < 32; ++i) amax = fmaxf(amax, fabsf(buf[blk * 32 + i] * g));
+            const uint32_t byte = mx_scale_byte(amax);
+            const float X = mx_scale_value(byte);
+            uint32_t* out = reinterpret_cast<uint32_t*>(qx + t * (int64_t)(d_e / 2) + blk * 16);
+            for (int wd = 0; wd < 4; ++wd) {
+                const float* bp = buf + blk * 32 + wd * 8;
+                const uint32_t word = mx_pack8(bp[0] * g, bp[1] * g, bp[2] * g, bp[3] * g, bp[4] * g, bp[5] * g,
+                                               bp[6] * g, bp[7] * g, X);
+                out[wd] = word;
+            }
+            ex[t * (int64_t)(d_e / 32) + blk] = (uint8_t)byte;
+        }
+        return;
+    }
 
     if (!zx) {
         float m = 0.f;
@@ -146,7 +166,7 @@ pme_status launch_rotate_generic(const RotateArgs& a) {
         if (e != hipSuccess) return PME_ERR_HIP;
         hipLaunchKernelGGL(kern, dim3((unsigned)a.T), dim3(kThreads), lds, a.stream,
                            (const float*)a.x, a.ldx, (int)a.d, (int)a.d_e, a.b, a.k, gamma,
-                           a.qx, a.sx, a.zx, a.xhat);
+                           a.qx, a.sx, a.zx, a.ex, a.xhat);
     } else {
         auto kern = k_rotate_generic<uint16_t>;
         if (lds > 64 * 1024)
@@ -154,7 +174,7 @@ pme_status launch_rotate_generic(const RotateArgs& a) {
         if (e != hipSuccess) return PME_ERR_HIP;
         hipLaunchKernelGGL(kern, dim3((unsigned)a.T), dim3(kThreads), lds, a.stream,
                            (const uint16_t*)a.x, a.ldx, (int)a.d, (int)a.d_e, a.b, a.k, gamma,
-                           a.qx, a.sx, a.zx, a.xhat);
+                           a.qx, a.sx, a.zx, a.ex, a.xhat);
     }
     return hip_status(hipGetLastError());
 }

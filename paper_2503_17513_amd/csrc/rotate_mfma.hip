@@ -48,11 +48,15 @@ template <int KLOG2> struct Layout {
         int c2 = (idx >> (NBITS - 2)) & 1, c3 = (idx >> (NBITS - 1)) & 1;
         return lo | (c2 << 2) | (c3 << 3) | (mid << 4);
     }
-    static constexpr int reg_of_run_pos(int j) {
-        for (int idx = 0; idx < NREG; ++idx)
-            if (run_pos(idx) == j) return idx;
-        return -1;
+    // inverse of run_pos as a constant table, so that an unrolled loop indexes registers with constants
+    struct Table { int v[NC / 4]; };
+    static constexpr Table make_table() {
+        Table t{};
+        for (int idx = 0; idx < NREG; ++idx) t.v[run_pos(idx)] = idx;
+        return t;
     }
+    static constexpr Table kRegOfRun = make_table();
+    static constexpr int reg_of_run_pos(int j) { return kRegOfRun.v[j]; }
 };
 
 __device__ __forceinline__ void swap16(float& r0, float& r1) {
@@ -228,13 +232,13 @@ __device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
 // Most waves a workgroup of this instantiation is launched with (bounds the registers per lane).
 template <int KLOG2, int TPW> constexpr int max_waves() { return (TPW == 1 && KLOG2 <= 8) ? kMaxWaves : kMaxWaves / 2; }
 
-enum { OUT_SYM = 0, OUT_ASYM = 1, OUT_XHAT = 2 };   // symmetric codes, asymmetric codes, fp32 rotated values
+enum { OUT_SYM = 0, OUT_ASYM = 1, OUT_XHAT = 2, OUT_MXFP4 = 3 };   // int4 symmetric / asymmetric codes, fp32 values, MXFP4
 
 template <int KLOG2, int TPW, bool F32IN, int OUT>
 __global__ void __launch_bounds__((64 * max_waves<KLOG2, TPW>()))
 k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, int b, int ks_count, int slot,
               double gamma, uint8_t* __restrict__ qx, float* __restrict__ sx, int32_t* __restrict__ zx,
-              float* __restrict__ xhat) {
+              uint8_t* __restrict__ ex, float* __restrict__ xhat) {
     using L = Layout<KLOG2>;
     constexpr int NC = L::NC, MT = L::MT, NREG = L::NREG;
     constexpr int NS = F32IN ? 3 : 1;
@@ -400,7 +404,60 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
                 }
             }
         }
-        if constexpr (OUT != OUT_XHAT) {
+        if constexpr (OUT == OUT_MXFP4) {
+            // ---- OCP MXFP4: one E8M0 scale per 32 consecutive outputs, E2M1 elements (round half to even,
+            //      saturating) by the hardware conversion.  A lane's run of RUN outputs holds whole blocks
+            //      when RUN >= 32; otherwise the block is shared with the lanes that differ in lane bit 4
+            //      (and bit 5 for 2^k = 32).
+            const float gf = (float)gamma;
+            constexpr int PER = L::RUN >= 32 ? 32 : L::RUN;        // values of one block held by this lane
+            constexpr int NBLK = L::RUN / PER;
+#pragma unroll
+            for (int ti = 0; ti < TPW; ++ti) {
+                if ((wave * TPW + ti) * 16 >= b) continue;
+                const int ap = (wave * TPW + ti) * 16 + l15;
+                uint32_t words[L::RUN / 8];
+                uint32_t bytes[NBLK];
+#pragma unroll
+                for (int blk = 0; blk < NBLK; ++blk) {
+                    float amax = 0.f;
+#pragma unroll
+                    for (int j = 0; j < PER; j += 2)
+                        amax = __builtin_fmaxf(__builtin_fmaxf(amax, __builtin_fabsf(v[ti][L::reg_of_run_pos(blk * PER + j)])),
+                                               __builtin_fabsf(v[ti][L::reg_of_run_pos(blk * PER + j + 1)]));
+                    if (L::RUN < 32) amax = fmaxf(amax, __shfl_xor(amax, 16));
+                    if (L::RUN < 16) amax = fmaxf(amax, __shfl_xor(amax, 32));
+                    bytes[blk] = mx_scale_byte(amax * gf);
+                    const float X = mx_scale_value(bytes[blk]);
+#pragma unroll
+                    for (int wd = 0; wd < PER / 8; ++wd) {
+#define PME_V(J) (v[ti][L::reg_of_run_pos(blk * PER + wd * 8 + (J))] * gf)
+                        const uint32_t word = mx_pack8(PME_V(0), PME_V(1), PME_V(2), PME_V(3), PME_V(4), PME_V(5), PME_V(6), PME_V(7), X);
+#undef PME_V
+                        words[blk * (PER / 8) + wd] = word;
+                    }
+                }
+                if (ap < b) {
+                    uint8_t* o = qx + t * (int64_t)(d_e / 2) + (((int64_t)ap * NC + c0) >> 1);
+                    if constexpr (L::RUN / 8 == 1) {
+                        *reinterpret_cast<uint32_t*>(o) = words[0];
+                    } else if constexpr (L::RUN / 8 == 2) {
+                        *reinterpret_cast<u32x2*>(o) = u32x2{words[0], words[1]};
+                    } else {
+#pragma unroll
+                        for (int wd = 0; wd < L::RUN / 8; wd += 4)
+                            *reinterpret_cast<u32x4*>(o + 4 * wd) = u32x4{words[wd], words[wd + 1], words[wd + 2], words[wd + 3]};
+                    }
+                    const bool owner = (L::RUN >= 32) || (L::RUN == 16 && l4 == 0) || (l4 == 0 && l5 == 0);
+                    if (owner) {
+                        uint8_t* eo = ex + t * (int64_t)(d_e / 32) + (((int64_t)ap * NC + c0) >> 5);
+#pragma unroll
+                        for (int blk = 0; blk < NBLK; ++blk) eo[blk] = (uint8_t)bytes[blk];
+                    }
+                }
+            }
+        }
+        if constexpr (OUT == OUT_SYM || OUT == OUT_ASYM) {
         // ---- per-token range
         float hi = 0.f, lo = 0.f;
         if constexpr (OUT == OUT_ASYM) {
@@ -494,7 +551,7 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
                 }
             }
         }
-        }   // OUT != OUT_XHAT
+        }   // int4 outputs
     }
     wait_all_vm();
 }
@@ -522,13 +579,14 @@ pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     const unsigned grid = (unsigned)std::min<int64_t>(a.T, 256 * (int64_t)occ);
     const double gamma = 1.0 / sqrt((double)a.d_e);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * nwaves), lds, a.stream, a.x, a.ldx, (int)a.T, (int)a.d,
-                       (int)a.d_e, a.b, ks, slot, gamma, a.qx, a.sx, a.zx, a.xhat);
+                       (int)a.d_e, a.b, ks, slot, gamma, a.qx, a.sx, a.zx, a.ex, a.xhat);
     return hip_status(hipGetLastError());
 }
 
 template <int KLOG2, int TPW, bool F32IN>
 pme_status launch_one(const RotateArgs& a, int ks, int nwaves) {
     if (a.xhat) return launch_out<KLOG2, TPW, F32IN, OUT_XHAT>(a, ks, nwaves);
+    if (a.ex) return launch_out<KLOG2, TPW, F32IN, OUT_MXFP4>(a, ks, nwaves);
     if (a.zx) return launch_out<KLOG2, TPW, F32IN, OUT_ASYM>(a, ks, nwaves);
     return launch_out<KLOG2, TPW, F32IN, OUT_SYM>(a, ks, nwaves);
 }

@@ -102,7 +102,7 @@ def test_expanded_linear_argument_errors():
     f = pme.lib().pme_expanded_linear
     need = pme.workspace_bytes(4, 64, 80, 8)
     assert need == 256 + 256
-    assert pme.workspace_bytes(2048, 2048, 2176, 3072) == 2048 * 1088 + 2048 * 4
+    assert pme.workspace_bytes(2048, 2048, 2176, 3072) == 2048 * 1088 + 2048 * 68   # codes + MXFP4 scale bytes
     assert pme.workspace_bytes(4, 81, 80, 8) == 0
 
     def call(x=FAKE, xt=1, T=4, d=64, ldx=64, d_e=80, qw=FAKE, sw=FAKE, N=8, y=FAKE, ldy=8, ws=FAKE, wsb=need):

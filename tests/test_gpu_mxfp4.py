@@ -1,0 +1,150 @@
+"""GPU parity of the MXFP4 path (paper Section 4, second quantization setting) against the CPU oracle."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+import paper_2503_17513_amd as pme
+from parity_util import check_xhat, to_device
+from workloads import custom_spec, make_workload
+
+pytestmark = pytest.mark.gpu
+GENERIC, MFMA = pme.PATH_GENERIC, pme.PATH_MFMA
+
+
+@pytest.fixture(autouse=True)
+def _reset():
+    yield
+    pme.set_path(pme.PATH_AUTO)
+    pme.set_gemm_tile(0)
+
+
+def _acts(T, d, d_e, in_dtype="bf16", seed=0):
+    spec = custom_spec(T, d, d_e, 8, in_dtype=in_dtype, act_dist="student_t3", outlier_frac=0.01, outlier_gain=50.0, seed=seed)
+    return make_workload(spec, weights=False).x
+
+
+def check_mx_quant(qx: torch.Tensor, ex: torch.Tensor, ref_x: np.ndarray):
+    """Scale bytes equal except where the block maximum sits within 1e-5 of a power of two; on blocks with
+    equal scales the codes are equal except neighbouring-value flips at rounding ties (<= 1e-4 of the codes)."""
+    q_ref, e_ref = oracle.quantize_mxfp4(ref_x)
+    q = oracle.unpack_fp4(qx.cpu().numpy())
+    e = ex.cpu().numpy()
+    D, M = ref_x.shape
+    bad = e != e_ref
+    if bad.any():
+        amax = np.max(np.abs(ref_x.reshape(D, M // 32, 32)), axis=2)[bad]
+        frac, _ = np.frexp(amax)
+        assert np.all(np.minimum(np.abs(frac - 0.5), np.abs(frac - 1.0)) < 1e-5), "scale byte differs away from a power of two"
+        assert np.all(np.abs(e.astype(int) - e_ref.astype(int))[bad] == 1)
+        assert bad.sum() <= max(1, int(1e-5 * bad.size))
+    same = np.repeat(~bad, 32, axis=1)
+    flips = (q != q_ref) & same
+    n = int(flips.sum())
+    if n:
+        X = np.repeat(np.ldexp(1.0, e_ref.astype(np.int64) - 127), 32, axis=1)
+        scaled = np.abs(ref_x / X)[flips]
+        mids = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])
+        dist = np.min(np.abs(scaled[:, None] - mids[None, :]), axis=1)
+        assert np.all(dist < 5e-4), f"a flipped code is not at a rounding tie ({dist.max():.3e})"
+        dec_gap = np.abs(oracle.e2m1_decode(q[flips]) - oracle.e2m1_decode(q_ref[flips]))
+        assert np.all(dec_gap <= 2.0)
+        assert n <= max(1, int(1e-4 * q.size)), f"{n} flipped codes of {q.size}"
+    return n
+
+
+QUANT_CASES = [
+    ("b12_k3_generic", 9, 80, 96, "f32", (GENERIC,)),
+    ("b68_k5", 21, 2048, 2176, "bf16", (GENERIC, MFMA)),
+    ("b132_k6", 8, 8192, 8448, "bf16", (GENERIC, MFMA)),
+    ("b68_k7", 9, 8192, 8704, "bf16", (GENERIC, MFMA)),
+    ("b60_k8", 5, 14336, 15360, "bf16", (GENERIC, MFMA)),
+    ("b20_k9", 3, 8192, 10240, "bf16", (GENERIC, MFMA)),
+    ("f32_b68_k5", 6, 2048, 2176, "f32", (GENERIC, MFMA)),
+    ("many_tokens_k7", 530, 8192, 8704, "bf16", (MFMA,)),
+]
+
+
+@pytest.mark.parametrize("name,T,d,d_e,in_dtype,paths", QUANT_CASES, ids=[c[0] for c in QUANT_CASES])
+def test_rotate_and_quantize_mxfp4(name, T, d, d_e, in_dtype, paths):
+    x = _acts(T, d, d_e, in_dtype, seed=len(name))
+    if T > 2:
+        x[1] = 0.0
+        x[2] = 0.0
+        x[2, d // 3] = 1.0
+    xd = to_device(x, in_dtype)
+    ref = oracle.rotate_structured(x, d_e)
+    for path in paths:
+        pme.set_path(path)
+        qx, ex = pme.hadamard_expand_quant_mxfp4(xd, d_e)
+        torch.cuda.synchronize()
+        check_mx_quant(qx, ex, ref)
+        if T > 2:
+            assert int(ex[1].max()) == 0 and int(qx[1].max()) == 0     # all-zero token: smallest scale, zero codes
+
+
+def test_mxfp4_rejects_d_e_not_multiple_of_32():
+    x = torch.zeros((4, 64), dtype=torch.float32, device="cuda")
+    with pytest.raises(pme.PmeError) as e:
+        pme.hadamard_expand_quant_mxfp4(x, 80)
+    assert e.value.status == 2
+
+
+def check_mx_gemm(y_gpu, qx, ex, qw, ew):
+    """bf16 rounding (1e-2 relative) plus fp32 accumulation inside the matrix core, bounded by 2^-18 of the
+    sum of the magnitudes of the terms (K <= 2^14 terms, error grows like sqrt(K) 2^-24 of that sum)."""
+    y_ref, abs_sum = oracle.gemm_mxfp4(qx, ex, qw, ew, return_abs=True)
+    err = np.abs(y_gpu.astype(np.float64) - y_ref)
+    assert np.all(err <= 1e-2 * np.abs(y_ref) + 2.0 ** -18 * abs_sum), f"worst {np.max(err / (np.abs(y_ref) + 1e-30)):.3e}"
+
+
+GEMM_CASES = [("small_ragged", 50, 70, 96, (GENERIC,)), ("one_k_step", 40, 72, 128, (GENERIC, MFMA)),
+              ("ragged_tiles", 300, 200, 2176, (GENERIC, MFMA)), ("wide_rows", 260, 520, 1280, (GENERIC, MFMA)),
+              ("c2_shape_rows", 2048, 384, 2176, (MFMA,)), ("big_tile", 1024, 4096, 512, (MFMA,))]
+
+
+@pytest.mark.parametrize("name,T,N,d_e,paths", GEMM_CASES, ids=[c[0] for c in GEMM_CASES])
+def test_mxfp4_gemm(name, T, N, d_e, paths):
+    rng = np.random.default_rng(T + N)
+    qx = rng.integers(0, 16, size=(T, d_e), dtype=np.uint8)
+    qw = rng.integers(0, 16, size=(N, d_e), dtype=np.uint8)
+    ex = rng.integers(118, 132, size=(T, d_e // 32), dtype=np.uint8)
+    ew = rng.integers(118, 130, size=(N, d_e // 32), dtype=np.uint8)
+    args = [torch.from_numpy(a).cuda() for a in (oracle.pack_fp4(qx), ex, oracle.pack_fp4(qw), ew)]
+    for path in paths:
+        pme.set_path(path)
+        y = pme.mxfp4_gemm(*args).to(torch.float32).cpu().numpy()
+        check_mx_gemm(y, qx, ex, qw, ew)
+
+
+@pytest.mark.parametrize("tile", range(1, 10))
+def test_mxfp4_gemm_every_tile(tile):
+    rng = np.random.default_rng(tile)
+    T, N, d_e = 300, 520, 1280
+    qx = rng.integers(0, 16, size=(T, d_e), dtype=np.uint8)
+    qw = rng.integers(0, 16, size=(N, d_e), dtype=np.uint8)
+    ex = rng.integers(120, 130, size=(T, d_e // 32), dtype=np.uint8)
+    ew = rng.integers(120, 130, size=(N, d_e // 32), dtype=np.uint8)
+    args = [torch.from_numpy(a).cuda() for a in (oracle.pack_fp4(qx), ex, oracle.pack_fp4(qw), ew)]
+    pme.set_path(MFMA)
+    pme.set_gemm_tile(100 + tile)
+    y = pme.mxfp4_gemm(*args).to(torch.float32).cpu().numpy()
+    check_mx_gemm(y, qx, ex, qw, ew)
+
+
+@pytest.mark.parametrize("shape", ((40, 2048, 2176, 200), (130, 8192, 8704, 300)))
+def test_mxfp4_layer_end_to_end(shape):
+    T, d, d_e, N = shape
+    rng = np.random.default_rng(5)
+    x = _acts(T, d, d_e, "bf16", seed=2)
+    W = (rng.standard_normal((d, N)) / np.sqrt(d)).astype(np.float32)
+    xd = to_device(x, "bf16")
+    wt = torch.from_numpy(np.ascontiguousarray(W.T)).cuda()
+    qw, ew = pme.hadamard_expand_quant_mxfp4(wt, d_e)          # offline weight side: rows of W^T
+    check_mx_quant(qw, ew, oracle.expand_weight(W, d_e).T)
+    y = pme.expanded_linear_mxfp4(xd, d_e, qw, ew).to(torch.float32).cpu().numpy()
+    qx, ex = pme.hadamard_expand_quant_mxfp4(xd, d_e)
+    check_mx_quant(qx, ex, oracle.rotate_structured(x, d_e))
+    check_mx_gemm(y, oracle.unpack_fp4(qx.cpu().numpy()), ex.cpu().numpy(), oracle.unpack_fp4(qw.cpu().numpy()), ew.cpu().numpy())
+    ref = x.astype(np.float64) @ W.astype(np.float64)
+    assert np.linalg.norm(y - ref) / np.linalg.norm(ref) < 0.25
