@@ -78,7 +78,7 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     constexpr int STAGE = ROWS * RB;
     constexpr int NSUB = RB / 32;                 // sub-steps of 64 codes per K step
     constexpr int SLAB = 32 * WN * 2;             // epilogue: one 32-token slab of the wave tile in bf16
-    static_assert(NW * SLAB <= NSTAGE * STAGE, "epilogue staging must fit in the K-loop stages");
+    static_assert(NW * SLAB + ROWS * 4 <= NSTAGE * STAGE, "epilogue staging must fit in the K-loop stages");
     static_assert(NSTAGE == 2 || NSTAGE == 3, "two or three stages");
 
     extern __shared__ __align__(1024) unsigned char smem[];      // NSTAGE stages
@@ -104,6 +104,21 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
         const uint8_t* base = (r < BM) ? qx + (int64_t)min(m0 + r, T - 1) * kb
                                        : qw + (int64_t)min(n0 + r - BM, N - 1) * kb;
         src[s] = base + kc * 16;
+    }
+    // The tile's scales are fetched now and stay in registers through the K loop, so that the epilogue does
+    // not start with a dependent round trip to memory: sx (times 1/256, which removes the 16 x 16 of the
+    // nibble trick exactly) for the BM tokens, then sw for the BN channels.
+    constexpr int NT = 64 * NW;
+    constexpr int PRE = (ROWS + NT - 1) / NT;
+    float pre[PRE];
+    if constexpr (MODE != MODE_I32) {
+#pragma unroll
+        for (int q = 0; q < PRE; ++q) {
+            const int idx = tid + NT * q;
+            pre[q] = 0.f;
+            if (idx < BM) pre[q] = sx[min(m0 + idx, T - 1)] * (1.f / 256.f);
+            else if (idx < ROWS) pre[q] = sw[min(n0 + idx - BM, N - 1)];
+        }
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(PME_AS3 unsigned char*)smem;
     auto issue = [&](int stage, int kt) {
@@ -254,23 +269,31 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     } else {
         // all waves are past the last barrier of the K loop: the stages are free for staging
         unsigned char* slab = smem + (size_t)wave * SLAB;
+        float* sc = reinterpret_cast<float*>(smem + (size_t)NW * SLAB);     // [BM] token scales, [BN] channel scales
+#pragma unroll
+        for (int q = 0; q < PRE; ++q) {
+            const int idx = tid + NT * q;
+            if (idx < ROWS) sc[idx] = pre[q];
+        }
+        lds_barrier();
         f32x4 swv[FN][4];
         int wsv[FN][4][4];
 #pragma unroll
         for (int j = 0; j < FN; ++j)
 #pragma unroll
-            for (int eg = 0; eg < 4; ++eg)
+            for (int eg = 0; eg < 4; ++eg) {
+                swv[j][eg] = *reinterpret_cast<const f32x4*>(sc + BM + wn * WN + 32 * j + 8 * eg + 4 * fk);
+                if (MODE == MODE_ASYM) {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int n = min(n0 + wn * WN + 32 * j + 8 * eg + 4 * fk + q, N - 1);
-                    swv[j][eg][q] = sw[n];
-                    if (MODE == MODE_ASYM) wsv[j][eg][q] = wsum[n];
+                    for (int q = 0; q < 4; ++q)
+                        wsv[j][eg][q] = wsum[min(n0 + wn * WN + 32 * j + 8 * eg + 4 * fk + q, N - 1)];
                 }
+            }
         uint16_t* y = static_cast<uint16_t*>(out);
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
             const int t = min(m0 + wm * WM + 32 * i + frow, T - 1);
-            const float sxs = sx[t] * (1.f / 256.f);          // exact: removes the 16 x 16 of the nibble trick
+            const float sxs = sc[wm * WM + 32 * i + frow];
             int zoff = 0;
             if (MODE == MODE_ASYM) zoff = (zx[t] - 8) * 256;
 #pragma unroll

@@ -325,6 +325,7 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
     }
     const int l4 = (lane >> 4) & 1, l5 = lane >> 5;
     const int c0 = run_start<KLOG2>(l4, l5);
+    const float g7 = (float)(gamma / 7.0);
 
     for (; t < T; t += gridDim.x) {
         if constexpr (F32IN) {
@@ -490,8 +491,8 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
         int z = 0;
         if constexpr (OUT == OUT_SYM) {
             if (hi > 0.f) {
-                s = (float)((double)hi * gamma / 7.0);
-                rinv = (float)(gamma / (double)s);
+                s = hi * g7;                      // absmax * gamma / 7
+                rinv = 7.f * __builtin_amdgcn_rcpf(hi);
             }
             if (tid == 0) sx[t] = s;
         } else {

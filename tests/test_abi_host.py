@@ -118,6 +118,42 @@ def test_expanded_linear_argument_errors():
     assert call(T=0, x=None, ws=None, wsb=0) == OK
 
 
+def test_mxfp4_and_weight_argument_errors():
+    L = pme.lib()
+    f = L.pme_hadamard_expand_quant_mxfp4
+    assert f(None, 1, 4, 64, 64, 96, FAKE, FAKE, None) == NULL
+    assert f(FAKE, 1, 4, 64, 64, 96, None, FAKE, None) == NULL
+    assert f(FAKE, 1, 4, 64, 64, 96, FAKE, None, None) == NULL
+    assert f(FAKE, 1, 4, 64, 64, 80, FAKE, FAKE, None) == SHAPE           # d_e not a multiple of 32
+    assert f(FAKE, 1, 4, 64, 64, 100, FAKE, FAKE, None) == ORDER
+    assert f(FAKE, 3, 4, 64, 64, 96, FAKE, FAKE, None) == DTYPE
+    assert f(None, 1, 0, 64, 64, 96, None, None, None) == OK
+    g = L.pme_mxfp4_gemm
+    assert g(None, FAKE, FAKE, FAKE, 4, 96, 8, FAKE, 8, None) == NULL
+    assert g(FAKE, None, FAKE, FAKE, 4, 96, 8, FAKE, 8, None) == NULL
+    assert g(FAKE, FAKE, FAKE, None, 4, 96, 8, FAKE, 8, None) == NULL
+    assert g(FAKE, FAKE, FAKE, FAKE, 4, 80, 8, FAKE, 8, None) == SHAPE
+    assert g(FAKE, FAKE, FAKE, FAKE, 4, 96, 8, FAKE, 7, None) == SHAPE
+    assert g(FAKE + 1, FAKE, FAKE, FAKE, 4, 96, 8, FAKE, 8, None) == ALIGN
+    assert g(FAKE, FAKE, FAKE, FAKE, 0, 96, 8, FAKE, 8, None) == OK
+    h = L.pme_expanded_linear_mxfp4
+    need = pme.workspace_bytes(4, 64, 96, 8)
+    assert h(FAKE, 1, 4, 64, 64, 96, FAKE, FAKE, 8, FAKE, 8, FAKE, need - 1, None) == WORKSPACE
+    assert h(FAKE, 1, 4, 64, 64, 96, FAKE, None, 8, FAKE, 8, FAKE, need, None) == NULL
+    assert h(FAKE, 1, 4, 64, 64, 80, FAKE, FAKE, 8, FAKE, 8, FAKE, need, None) == SHAPE
+    w = L.pme_expand_quantize_weights
+    assert w(None, 0, 8, 64, 64, 80, FAKE, FAKE, None) == NULL
+    assert w(FAKE, 0, 8, 64, 60, 80, FAKE, FAKE, None) == SHAPE
+    r = L.pme_weight_rowsum
+    assert r(None, 8, 80, FAKE, None) == NULL
+    assert r(FAKE, 8, 81, FAKE, None) == SHAPE
+    a = L.pme_w4a4_gemm_asym
+    assert a(FAKE, FAKE, None, FAKE, FAKE, FAKE, 4, 80, 8, FAKE, 8, None) == NULL
+    assert a(FAKE, FAKE, FAKE, FAKE, FAKE, None, 4, 80, 8, FAKE, 8, None) == NULL
+    q = L.pme_hadamard_expand_quant_asym
+    assert q(FAKE, 1, 4, 64, 64, 80, FAKE, FAKE, None, None) == NULL
+
+
 def test_probe_copy_errors():
     f = pme.lib().pme_probe_copy
     assert f(None, FAKE, 16, None) == NULL
