@@ -97,10 +97,12 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     // DMA source of each 16-byte chunk this lane moves: block blk covers tile rows RPB blk .. RPB blk + RPB - 1;
     // lane L writes chunk position L % CPR of row RPB blk + L / CPR, which holds chunk (L % CPR) ^ swz(row).
     const uint8_t* src[CH];
+    int kcl[CH];          // logical chunk each DMA slot of this lane carries (for the shortened last K step)
 #pragma unroll
     for (int s = 0; s < CH; ++s) {
         const int r = RPB * ((wave + NW * s) % BLKS) + lane / CPR;
         const int kc = (lane % CPR) ^ swz<RB>(r);
+        kcl[s] = kc;
         const uint8_t* base = (r < BM) ? qx + (int64_t)min(m0 + r, T - 1) * kb
                                        : qw + (int64_t)min(n0 + r - BM, N - 1) * kb;
         src[s] = base + kc * 16;
@@ -121,11 +123,18 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
         }
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(PME_AS3 unsigned char*)smem;
+    // K steps: whole steps of RB bytes, the last one possibly half as long (kb is a multiple of 64): its DMA
+    // leaves out the chunks beyond the row end and its sub-steps beyond TAIL_SUB are not computed.
+    const int KT = (kb + RB - 1) / RB;
+    const int tail_chunks = (kb - (KT - 1) * RB) / 16;          // chunks of the last K step
+    const int tail_sub = tail_chunks / 2;                       // its sub-steps (64 codes = 2 chunks each)
     auto issue = [&](int stage, int kt) {
+        const int lim = (kt == KT - 1) ? tail_chunks : CPR;
 #pragma unroll
         for (int s = 0; s < CH; ++s)
-            dma16(src[s] + (int64_t)kt * RB,
-                  __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + ((wave + NW * s) % BLKS) * 1024));
+            if (kcl[s] < lim)
+                dma16(src[s] + (int64_t)kt * RB,
+                      __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + ((wave + NW * s) % BLKS) * 1024));
     };
 
     i32x16 acc[FM][FN];
@@ -209,7 +218,6 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     // start the DMA of K step kt + NSTAGE into that stage.  Every K step issues the same number of DMA
     // instructions (beyond the end the last step is loaded again into a stage nobody reads), so the
     // wait count is a constant: the NSTAGE - 2 newest groups may still be in flight.
-    const int KT = kb / RB;
 #pragma unroll
     for (int st = 0; st < NSTAGE; ++st) issue(st, min(st, KT - 1));
     wait_vm<(NSTAGE - 1) * CH>();
@@ -243,10 +251,11 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
         const unsigned char* scur = smem + cur * STAGE;
 #pragma unroll
         for (int s = 0; s < NSUB; ++s) {
-            if (s + 2 < NSUB) load_frags(raw[s & 1], scur, s + 2);
-            if (s + 1 < NSUB) unpack(raw[(s + 1) & 1], unp[(s + 1) & 1]);
-            mfma_all(unp[s & 1]);
-            interleave(s + 2 < NSUB);
+            if (s < tail_sub) {                              // wave-uniform
+                if (s + 2 < tail_sub) load_frags(raw[s & 1], scur, s + 2);
+                if (s + 1 < tail_sub) unpack(raw[(s + 1) & 1], unp[(s + 1) & 1]);
+                mfma_all(unp[s & 1]);
+            }
         }
     }
     wait_vm<0>();
@@ -338,7 +347,7 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
 template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE>
 pme_status launch_tile(const GemmArgs& a) {
     const int kb = (int)(a.d_e / 2);
-    if (kb % RB) return PME_ERR_UNSUPPORTED_PATH;
+    if (kb % 64) return PME_ERR_UNSUPPORTED_PATH;      // whole sub-steps; the last K step may be half as long
     const int tiles_m = (int)((a.T + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WGM * WGN);
     const size_t lds = (size_t)NSTAGE * (BM + BN) * RB;
@@ -375,8 +384,10 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
     auto tiles = [&](int bm, int bn) { return ((a.T + bm - 1) / bm) * ((a.N + bn - 1) / bn); };
     int id = g_tile_override;
     if (id == 0) {
-        // The largest tile that still gives every one of the 256 compute units a workgroup; whole
-        // 128-byte lines per row and K step where d_e allows (measured faster on MI355X).
+        // The largest tile that still gives every one of the 256 compute units a workgroup, with whole
+        // 128-byte lines per row and K step (measured faster on MI355X than 64-byte steps).
+        // (a half-length last step is supported but measured no faster than 64-byte steps, so those are kept
+        // when d_e is not a multiple of 256)
         const bool wide = (a.d_e % 256) == 0;
         if (tiles(256, 256) >= cus) id = wide ? 11 : 8;
         else if (tiles(128, 256) >= cus) id = wide ? 16 : 2;

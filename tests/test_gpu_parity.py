@@ -158,12 +158,13 @@ def test_gemm_accumulators_and_epilogue(name, T, N, d_e, paths):
         check_bf16(y, y_ref)
 
 
+@pytest.mark.parametrize("d_e", (1280, 1152, 128))
 @pytest.mark.parametrize("tile", range(1, 19))
-def test_gemm_every_tile_configuration(tile):
-    # every entry of the MFMA kernel's tile table, forced through the tuning hook: ragged T and N,
-    # 5 K steps of 128 bytes (10 of 64), extreme rows
+def test_gemm_every_tile_configuration(tile, d_e):
+    # every entry of the MFMA kernel's tile table, forced through the tuning hook: ragged T and N; K of
+    # 5 whole steps of 128 bytes, of 4.5 (a half-length last step), and of a single half step; extreme rows
     rng = np.random.default_rng(tile)
-    T, N, d_e = 300, 520, 1280
+    T, N = 300, 520
     q = rng.integers(-7, 8, size=(T, d_e), dtype=np.int8)
     qw = rng.integers(-8, 8, size=(N, d_e), dtype=np.int8)
     q[0] = -7
