@@ -22,7 +22,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2;
 #define PME_AS3 __attribute__((address_space(3)))
 
 template <int RB> __device__ __forceinline__ int swz(int r) {
-    return RB == 64 ? (((r >> 1) ^ (r >> 3)) & 3) : ((r >> 1) & 7);
+    return RB == 64 ? (((r >> 2) ^ r) & 3) : (r & 7);
 }
 __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory"); }
 template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
