@@ -20,6 +20,7 @@
 
 #include <algorithm>
 #include <mutex>
+#include <type_traits>
 
 namespace pme {
 namespace {
@@ -222,8 +223,9 @@ __device__ __forceinline__ void wait_all_vm() { asm volatile("s_waitcnt vmcnt(0)
 // 16 bytes per lane from global memory into LDS at lds_base + 16 * lane (lds_base wave-uniform); lanes
 // switched off by the caller's branch move nothing.  Overwrites M0, which the compiler does not keep
 // values in; no other code in this kernel makes the compiler emit an M0 use.
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base) {
+    // wave-uniform 64-bit base in SGPRs plus a 32-bit byte offset per lane
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory");
 }
 
 // One workgroup handles tokens blockIdx.x, blockIdx.x + gridDim.x, ...  The token buffer in LDS is
@@ -268,14 +270,24 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
     const uint32_t lds0 = (uint32_t)(uintptr_t)(PME_AS3 unsigned char*)smem;
 
     // bf16 token: HBM -> LDS by DMA, 16 bytes per lane, laid out for the transposing reads
+    // Chunk p = 64 (wave + nwaves s) + lane of the LDS image holds the 8 inputs (a, c .. c + 7) with, for
+    // blk = p / 8 and r = p % 8, a = 4 (blk / MT) + r / 2 and c = 16 (blk % MT) + 8 (r % 2).  Because the
+    // 64-chunk base is a multiple of 8 blocks, the byte offset of that chunk in the token splits into a
+    // per-lane constant (the offset for base 0) and a wave-uniform part, so each DMA costs one vector add.
+    uint32_t lane_off;
+    {
+        const int blk = lane >> 3, r = lane & 7;
+        const int a = 4 * (blk / MT) + (r >> 1), c = 16 * (blk % MT) + 8 * (r & 1);
+        lane_off = 2u * (uint32_t)(a * NC + c);
+    }
     auto load_token_dma = [&](int64_t t) {
         const unsigned char* xr = reinterpret_cast<const unsigned char*>(static_cast<const uint16_t*>(xv) + t * ldx);
         for (int base = wave * 64; base < nchunks; base += nwaves * 64) {
-            const int p = base + lane;
-            const int blk = p >> 3, r = p & 7;
-            const int a = 4 * (blk / MT) + (r >> 1), c = 16 * (blk % MT) + 8 * (r & 1);
-            const int i = a * NC + c;
-            if (p < nchunks && i < d) dma16(xr + 2 * (size_t)i, __builtin_amdgcn_readfirstlane(lds0 + base * 16));
+            const int b0 = base >> 3;                                    // first block of this DMA, wave-uniform
+            const uint32_t uni = 2u * (uint32_t)(4 * (b0 / MT) * NC + 16 * (b0 % MT));
+            const uint32_t off = lane_off + __builtin_amdgcn_readfirstlane(uni);
+            // chunks past the real rows have offsets of at least 2 d, so one comparison covers both ends
+            if (off < 2u * (uint32_t)d) dma16(xr, off, __builtin_amdgcn_readfirstlane(lds0 + base * 16));
         }
     };
     // fp32 token: split every input into three bf16 terms (exact sum) and store each term plane in
@@ -338,12 +350,8 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
 
         // ---- base block on the matrix cores: Z^T[c][a'] = sum_a X~[a][c] P[a][a']
         f32x4 acc[TPW][MT];
-#pragma unroll
-        for (int ti = 0; ti < TPW; ++ti)
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) acc[ti][mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-        for (int ks = 0; ks < ks_count; ++ks) {
+        auto base_block = [&](int ks, auto first) {     // first: the accumulators start from a literal zero
+            constexpr bool FIRST = decltype(first)::value;
             bf16x8 bfrag[TPW];
 #pragma unroll
             for (int ti = 0; ti < TPW; ++ti)
@@ -361,7 +369,8 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
                     const bf16x8 af = __builtin_bit_cast(bf16x8, both);
 #pragma unroll
                     for (int ti = 0; ti < TPW; ++ti)   // tiles beyond the block have all-zero B fragments
-                        acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfrag[ti], acc[ti][mt], 0, 0, 0);
+                        acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                            af, bfrag[ti], FIRST ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[ti][mt], 0, 0, 0);
                 } else {
 #pragma unroll
                     for (int sp = 0; sp < NS; ++sp) {
@@ -370,11 +379,14 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
                         const bf16x8 af = __builtin_bit_cast(bf16x8, raw);
 #pragma unroll
                         for (int ti = 0; ti < TPW; ++ti)
-                            acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(af, bfrag[ti], acc[ti][mt], 0, 0, 0);
+                            acc[ti][mt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(
+                                af, bfrag[ti], (FIRST && sp == 0) ? f32x4{0.f, 0.f, 0.f, 0.f} : acc[ti][mt], 0, 0, 0);
                     }
                 }
             }
-        }
+        };
+        base_block(0, std::true_type{});
+        for (int ks = 1; ks < ks_count; ++ks) base_block(ks, std::false_type{});
 
         if constexpr (!F32IN) {
             // every wave has read the token out of LDS: refill the buffer with the next token now
