@@ -67,7 +67,7 @@ __global__ void __launch_bounds__(64 * WGM * WGN)
 k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             const float* __restrict__ sx, const float* __restrict__ sw,
             const int32_t* __restrict__ zx, const int32_t* __restrict__ wsum,
-            int T, int N, int kb, void* __restrict__ out, int64_t ldo, int tiles_m, int tiles_n, int vec_store) {
+            int T, int N, int kb, void* __restrict__ out, int64_t ldo, int tiles_m, int tiles_n, int xcd_gm, int vec_store) {
     constexpr int NW = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
     constexpr int ROWS = BM + BN;
@@ -88,12 +88,8 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
 
-    // Workgroups are dealt round-robin to the 8 XCDs; give each XCD a contiguous range of tiles so
-    // that tiles sharing rows of qx / qw share an L2.
-    int tile = blockIdx.x;
-    const int ntiles = tiles_m * tiles_n;
-    if ((ntiles & 7) == 0) tile = (blockIdx.x & 7) * (ntiles >> 3) + (blockIdx.x >> 3);
-    const int tm = tile / tiles_n, tn = tile % tiles_n;
+    int tm, tn;
+    xcd_tile((int)blockIdx.x, tiles_m, tiles_n, xcd_gm, tm, tn);     // compact tile block per XCD
     const int m0 = tm * BM, n0 = tn * BN;
 
     // DMA source of each 16-byte chunk this lane moves: block blk covers tile rows RPB blk .. RPB blk + RPB - 1;
@@ -363,7 +359,7 @@ pme_status launch_tile(const GemmArgs& a) {
     const int vec = (a.N % 8 == 0 && a.ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0) ? 1 : 0;
 #define PME_LAUNCH(MODE)                                                                                        \
     hipLaunchKernelGGL((k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE>), grid, block, lds, a.stream, a.qx, a.qw, \
-                       a.sx, a.sw, a.zx, a.wsum, (int)a.T, (int)a.N, kb, a.y, a.ldy, tiles_m, tiles_n, vec)
+                       a.sx, a.sw, a.zx, a.wsum, (int)a.T, (int)a.N, kb, a.y, a.ldy, tiles_m, tiles_n, xcd_grid_m(tiles_m, tiles_n, BM, BN), vec)
     if (a.out_i32) PME_LAUNCH(MODE_I32);
     else if (a.zx) PME_LAUNCH(MODE_ASYM);
     else PME_LAUNCH(MODE_BF16);

@@ -44,7 +44,7 @@ template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE>
 __global__ void __launch_bounds__(64 * WGM * WGN)
 k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, const uint8_t* __restrict__ qw,
               const uint8_t* __restrict__ ew, int T, int N, int kb, int eb, uint16_t* __restrict__ y, int64_t ldo,
-              int tiles_m, int tiles_n, int vec_store) {
+              int tiles_m, int tiles_n, int xcd_gm, int vec_store) {
     constexpr int NW = WGM * WGN;
     constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
     constexpr int ROWS = BM + BN;
@@ -64,10 +64,8 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave / WGN, wn = wave % WGN;
-    int tile = blockIdx.x;
-    const int ntiles = tiles_m * tiles_n;
-    if ((ntiles & 7) == 0) tile = (blockIdx.x & 7) * (ntiles >> 3) + (blockIdx.x >> 3);   // contiguous tiles per XCD
-    const int tm = tile / tiles_n, tn = tile % tiles_n;
+    int tm, tn;
+    xcd_tile((int)blockIdx.x, tiles_m, tiles_n, xcd_gm, tm, tn);     // compact tile block per XCD
     const int m0 = tm * BM, n0 = tn * BN;
 
     const uint8_t* src[CH];
@@ -239,7 +237,7 @@ pme_status launch_tile(const MxGemmArgs& a) {
         return PME_ERR_HIP;
     const int vec = (a.N % 8 == 0 && a.ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0) ? 1 : 0;
     hipLaunchKernelGGL(kern, grid, block, lds, a.stream, a.qx, a.ex, a.qw, a.ew, (int)a.T, (int)a.N, kb, eb,
-                       static_cast<uint16_t*>(a.y), a.ldy, tiles_m, tiles_n, vec);
+                       static_cast<uint16_t*>(a.y), a.ldy, tiles_m, tiles_n, xcd_grid_m(tiles_m, tiles_n, BM, BN), vec);
     return hip_status(hipGetLastError());
 }
 

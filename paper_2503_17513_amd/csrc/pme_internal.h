@@ -60,6 +60,30 @@ void set_mxgemm_tile_override(int id);
 
 inline pme_status hip_status(hipError_t e) { return e == hipSuccess ? PME_OK : PME_ERR_HIP; }
 
+// Workgroup -> output tile map of the tiled GEMMs.  Workgroups are dealt round-robin to the 8 XCDs, each with
+// an L2 of its own, so XCD x (= workgroup index % 8) gets a compact sub-grid of tiles: the XCDs form a
+// gm x (8 / gm) grid over the tile grid and XCD x walks its tiles_m / gm by tiles_n / (8 / gm) part row by row.
+// What one L2 must fetch is then (rows of qx + rows of qw) of that part rather than of whole tile rows.
+// xcd_grid_m picks gm (the split with the fewest operand rows per XCD); 0 = no split fits, identity map.
+inline int xcd_grid_m(int tiles_m, int tiles_n, int bm, int bn) {
+    int best = 0;
+    long best_rows = 0;
+    for (int gm = 1; gm <= 8; gm *= 2) {
+        const int gn = 8 / gm;
+        if (tiles_m % gm || tiles_n % gn) continue;
+        const long rows = (long)(tiles_m / gm) * bm + (long)(tiles_n / gn) * bn;
+        if (!best || rows < best_rows) { best = gm; best_rows = rows; }
+    }
+    return best;
+}
+__device__ __forceinline__ void xcd_tile(int wg, int tiles_m, int tiles_n, int gm, int& tm, int& tn) {
+    if (gm == 0) { tm = wg / tiles_n; tn = wg % tiles_n; return; }
+    const int gn = 8 / gm, pn = tiles_n / gn, pm = tiles_m / gm;
+    const int x = wg & 7, i = wg >> 3;
+    tm = (x / gn) * pm + i / pn;
+    tn = (x % gn) * pn + i % pn;
+}
+
 // Round-to-nearest-even float -> bf16 bits (finite inputs; NaN stays NaN).
 __device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
     uint32_t u = __float_as_uint(f);
