@@ -21,18 +21,22 @@ PEAK_INT8_TOPS = 5000.0      # MI355X dense int8 MFMA, published
 PEAK_HBM_GBS = 8000.0        # MI355X HBM3E, published
 
 
-def _event_ms(fn, iters: int) -> float:
-    """Average milliseconds per call of fn over `iters` back-to-back launches (HIP events on the
-    stream the library launches on: torch's current stream)."""
+def _event_ms(fn, iters: int, repeats: int = 1) -> float:
+    """Milliseconds per call of fn: `iters` back-to-back launches between two HIP events (recorded on the
+    stream the library launches on, torch's current stream); the median over `repeats` such runs."""
     import torch
-    start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    torch.cuda.synchronize()
-    start.record()
-    for _ in range(iters):
-        fn()
-    stop.record()
-    torch.cuda.synchronize()
-    return start.elapsed_time(stop) / iters
+    times = []
+    for _ in range(repeats):
+        start, stop = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        start.record()
+        for _ in range(iters):
+            fn()
+        stop.record()
+        torch.cuda.synchronize()
+        times.append(start.elapsed_time(stop) / iters)
+    times.sort()
+    return times[len(times) // 2]
 
 
 def _cpu_baseline(wl, budget_s: float = 20.0):
@@ -45,19 +49,38 @@ def _cpu_baseline(wl, budget_s: float = 20.0):
     except Exception:
         threads = len(os.sched_getaffinity(0))
     sp = wl.spec
+
+    def timed(tokens):
+        t0 = time.perf_counter()
+        oracle.expanded_linear(wl.x[:tokens], sp.d_e, wl.qw, wl.sw)
+        return time.perf_counter() - t0
+
     # grow the token sample until one pass takes a few seconds, capped at the full batch
     tokens = min(sp.T, 128)
     while True:
-        t0 = time.perf_counter()
-        oracle.expanded_linear(wl.x[:tokens], sp.d_e, wl.qw, wl.sw)
-        dt = time.perf_counter() - t0
-        if tokens >= sp.T or dt * 4 > budget_s:
+        dt = timed(tokens)
+        if tokens >= sp.T or dt * 4 > budget_s * 0.6:
             break
         tokens = min(sp.T, tokens * 4)
+    # a workload the oracle finishes quickly is passed over several times (about 10 s of work in all)
+    passes = max(1, min(10, int(budget_s * 0.5 / max(dt, 1e-3))))
+    if passes > 1:
+        dt = sum(timed(tokens) for _ in range(passes)) / passes
     ops = 2.0 * tokens * sp.d_e * sp.N
-    return {"value": ops / dt / 1e12, "unit": "TOPS", "cores": int(threads), "kind": "oracle",
-            "sample": f"{tokens} of {sp.T} tokens of {sp.name}, all {sp.N} outputs, one pass, {dt:.2f} s",
-            "host_cpus": len(os.sched_getaffinity(0))}
+    out = {"value": ops / dt / 1e12, "unit": "TOPS", "cores": int(threads), "kind": "oracle",
+           "sample": f"{tokens} of {sp.T} tokens of {sp.name}, all {sp.N} outputs, mean of {passes} pass(es) of {dt:.2f} s",
+           "host_cpus": len(os.sched_getaffinity(0))}
+    # the same oracle held to one thread, on a sample sized from the rate just seen
+    try:
+        from threadpoolctl import threadpool_limits
+        t1 = max(16, min(tokens, int(tokens * (budget_s * 0.3) / max(dt * threads, 1e-3))))
+        with threadpool_limits(limits=1):
+            dt1 = timed(t1)
+        out["single_thread"] = {"value": 2.0 * t1 * sp.d_e * sp.N / dt1 / 1e12, "unit": "TOPS", "cores": 1,
+                                "sample": f"{t1} tokens, one pass, {dt1:.2f} s"}
+    except ImportError:
+        pass
+    return out
 
 
 def main() -> int:
@@ -71,8 +94,13 @@ def main() -> int:
     ap.add_argument("--mxfp4", action="store_true",
                     help="also time the MXFP4 variant of the layer (the paper's second quantization setting)")
     ap.add_argument("--probe-copy", action="store_true",
-                    help="also run the library's plain 1 GiB copy kernel (the known-size dispatch that calibrates "
-                         "the profiler's FETCH_SIZE / WRITE_SIZE counters)")
+                    help="time the library's plain 1 GiB copy kernel with 5 launches instead of 2 (the known-size "
+                         "dispatch that calibrates the profiler's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--no-probes", action="store_true",
+                    help="skip the two measured ceilings (streaming copy, back-to-back matrix-core instructions)")
+    ap.add_argument("--cold", action="store_true",
+                    help="also time the layer cycling through distinct operand sets larger than twice the 256 MB "
+                         "last-level cache, so that nothing is served from cache")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)", file=sys.stderr)
@@ -102,9 +130,28 @@ def main() -> int:
 
     def stage_times(sp, b, iters):
         pme.hadamard_expand_quant(b["x"], sp.d_e, b["qx"], b["sx"])
-        t_rot = _event_ms(lambda: pme.hadamard_expand_quant(b["x"], sp.d_e, b["qx"], b["sx"]), iters)
-        t_gemm = _event_ms(lambda: pme.w4a4_gemm(b["qx"], b["sx"], b["qw"], b["sw"], b["y"]), iters)
+        t_rot = _event_ms(lambda: pme.hadamard_expand_quant(b["x"], sp.d_e, b["qx"], b["sx"]), iters, 5)
+        t_gemm = _event_ms(lambda: pme.w4a4_gemm(b["qx"], b["sx"], b["qw"], b["sw"], b["y"]), iters, 5)
         return t_rot, t_gemm
+
+    def measured_ceilings(fp4: bool, copy_launches: int):
+        """The two microbenchmarks the roofline fractions are also quoted against."""
+        res = {}
+        src = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda").fill_(1)
+        dst = torch.empty_like(src)
+        pme.probe_copy(src, dst)
+        t_copy = _event_ms(lambda: pme.probe_copy(src, dst), copy_launches)
+        res["probe_copy"] = {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "us": t_copy * 1e3,
+                             "gbs": 2 * (1 << 30) / (t_copy * 1e-3) / 1e9}
+        del src, dst
+        torch.cuda.empty_cache()
+        sink = torch.zeros((512 * 256,), dtype=torch.int32, device="cuda")
+        for kind, key in ((0, "probe_mfma_int8"),) + (((1, "probe_mfma_fp4"),) if fp4 else ()):
+            iters = 20000
+            n_ops = pme.probe_mfma(kind, sink, iters)
+            t = _event_ms(lambda: pme.probe_mfma(kind, sink, iters), 3)
+            res[key] = {"ops_per_launch": n_ops, "us": t * 1e3, "tops": n_ops / (t * 1e-3) / 1e12}
+        return res
 
     wl, b = prepare(args.workload)
     sp = wl.spec
@@ -149,6 +196,15 @@ def main() -> int:
             roof["traffic_detail"] = tr
     rot_bytes = algorithmic_bytes_rotate_quant(sp)
     rot_gbs = rot_bytes / (t_rot * 1e-3) / 1e9
+
+    probes = None
+    if not args.no_probes:
+        probes = measured_ceilings(args.mxfp4, 5 if args.probe_copy else 2)
+        if decode:
+            roof["measured_peak"] = probes["probe_copy"]["gbs"]
+        else:
+            roof["measured_peak"] = probes["probe_mfma_int8"]["tops"]
+        roof["frac_of_measured"] = roof["achieved"] / roof["measured_peak"]
 
     out = {
         "metric": "expanded W4A4 linear TOPS (prefill) + rotate/quant HBM GB/s (decode), 1 MI355X",
@@ -197,15 +253,30 @@ def main() -> int:
         out["mxfp4"] = {"layer_us": t_l * 1e3, "layer_tflops": ops / (t_l * 1e-3) / 1e12, "rotate_quant_us": t_r * 1e3,
                         "gemm_us": t_g * 1e3, "gemm_tflops": ops / (t_g * 1e-3) / 1e12, "gemm_peak_tflops": 10100.0,
                         "gemm_frac": ops / (t_g * 1e-3) / 1e12 / 10100.0}
-    if args.probe_copy:
-        src = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda").fill_(1)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            pme.probe_copy(src, dst)
-        t_copy = _event_ms(lambda: pme.probe_copy(src, dst), 5)
-        out["probe_copy"] = {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "us": t_copy * 1e3,
-                             "gbs": 2 * (1 << 30) / (t_copy * 1e-3) / 1e9}
-        del src, dst
+    if probes:
+        out["rotate_quant"]["measured_peak"] = probes["probe_copy"]["gbs"]
+        out["rotate_quant"]["frac_of_measured"] = rot_gbs / probes["probe_copy"]["gbs"]
+        out["measured_ceilings"] = probes
+        if args.mxfp4 and "probe_mfma_fp4" in probes:
+            out["mxfp4"]["gemm_measured_peak_tflops"] = probes["probe_mfma_fp4"]["tops"]
+    if args.cold:
+        per_set = (b["x"].numel() * b["x"].element_size() + b["qw"].numel() + b["y"].numel() * 2 + b["ws"].numel())
+        nsets = max(2, -(-(600 << 20) // per_set))
+        sets = [b] + [dict(x=b["x"].clone(), qw=b["qw"].clone(), sw=b["sw"], y=torch.empty_like(b["y"]),
+                           ws=torch.empty_like(b["ws"])) for _ in range(nsets - 1)]
+        state = {"i": 0}
+
+        def cold_step():
+            c = sets[state["i"] % nsets]
+            state["i"] += 1
+            pme.expanded_linear(c["x"], sp.d_e, c["qw"], c["sw"], c["y"], c["ws"])
+
+        for _ in range(nsets):
+            cold_step()
+        t_cold = _event_ms(cold_step, nsets * max(2, 200 // nsets), 3)
+        out["cold"] = {"layer_us": t_cold * 1e3, "layer_tops": ops / (t_cold * 1e-3) / 1e12, "operand_sets": nsets,
+                       "bytes_per_set": per_set}
+        del sets
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = _cpu_baseline(wl)
     print(json.dumps(out))

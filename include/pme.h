@@ -178,6 +178,15 @@ pme_status pme_base_block(int64_t b, int8_t* out_bxb);
  * the known-size kernel used to calibrate the profiler's HBM byte counters. */
 pme_status pme_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
 
+/* Back-to-back independent matrix-core instructions, nothing else in the loop: the measured ceiling the
+ * GEMMs are priced against next to the published peak.  kind 0: v_mfma_i32_32x32x32_i8 (the int4 path's
+ * instruction), kind 1: v_mfma_scale_f32_32x32x64_f8f6f4 on FP4 operands (the MXFP4 path's).  Launches 512
+ * workgroups of 256 threads, each wave issuing 4 * iters instructions; out: DEVICE int32, at least
+ * 512 * 256 elements (a checksum that keeps the loop alive); *ops (HOST, may be null) receives the operation
+ * count of one launch (2 per multiply-add).  PME_ERR_DTYPE for another kind, PME_ERR_SHAPE for a short
+ * buffer or iters outside [0, 2^24]. */
+pme_status pme_probe_mfma(int kind, int32_t* out, size_t out_elems, int iters, double* ops, void* stream);
+
 /* Tuning hook for benchmarks: force the MFMA GEMM's tile configuration (0 = choose from the shape;
  * 1..18 = a fixed entry of the int4 kernel's tile table, 100 + (1..9) = of the MXFP4 kernel's; 0 resets
  * both).  Process-wide, not thread-safe. */

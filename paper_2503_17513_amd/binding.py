@@ -17,7 +17,7 @@ F32, BF16 = 0, 1
 EXPORTS = ("pme_hadamard_expand_quant", "pme_expand_quantize_weights", "pme_hadamard_expand_quant_mxfp4",
            "pme_mxfp4_gemm", "pme_expanded_linear_mxfp4", "pme_hadamard_expand_quant_asym", "pme_w4a4_gemm", "pme_w4a4_gemm_asym",
            "pme_weight_rowsum", "pme_expanded_linear", "pme_workspace_bytes", "pme_hadamard_expand_f32",
-           "pme_w4a4_gemm_i32", "pme_factor_order", "pme_base_block", "pme_probe_copy", "pme_set_path", "pme_set_gemm_tile",
+           "pme_w4a4_gemm_i32", "pme_factor_order", "pme_base_block", "pme_probe_copy", "pme_probe_mfma", "pme_set_path", "pme_set_gemm_tile",
            "pme_get_path", "pme_status_string", "pme_version")
 
 
@@ -57,6 +57,7 @@ def lib() -> C.CDLL:
     L.pme_factor_order.argtypes = [i64, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     L.pme_base_block.argtypes = [i64, vp]
     L.pme_probe_copy.argtypes = [vp, vp, sz, vp]
+    L.pme_probe_mfma.argtypes = [i32, vp, sz, i32, C.POINTER(C.c_double), vp]
     L.pme_set_path.argtypes = [i32]
     L.pme_set_gemm_tile.argtypes = [i32]
     L.pme_set_gemm_tile.restype = None
@@ -271,6 +272,14 @@ def expanded_linear(x, d_e: int, qw, sw, y: torch.Tensor | None = None, workspac
 def probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
     nbytes = src.numel() * src.element_size()
     _check(lib().pme_probe_copy(_dev(src, "src"), _dev(dst, "dst"), nbytes, _stream()), "pme_probe_copy")
+
+
+def probe_mfma(kind: int, out: torch.Tensor, iters: int) -> float:
+    """Launch the matrix-core probe (kind 0 int8, 1 FP4) and return the operation count of the launch."""
+    ops = C.c_double(0.0)
+    _check(lib().pme_probe_mfma(int(kind), _dev(out, "out"), out.numel(), int(iters), C.byref(ops), _stream()),
+           "pme_probe_mfma")
+    return ops.value
 
 
 def pack_int4_codes(codes: torch.Tensor) -> torch.Tensor:

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 PKG = os.path.dirname(HERE)
 ROOT = os.path.dirname(PKG)
 OBJ = os.path.join(ROOT, "_build")
-SOURCES = ["pme_api.hip", "rotate_generic.hip", "rotate_mfma.hip", "gemm_generic.hip", "gemm_mfma.hip", "gemm_decode.hip", "gemm_mxfp4.hip"]
+SOURCES = ["pme_api.hip", "rotate_generic.hip", "rotate_mfma.hip", "gemm_generic.hip", "gemm_mfma.hip", "gemm_decode.hip", "gemm_mxfp4.hip", "probes.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops", "-Wno-unused-command-line-argument"]
 LIB = os.path.join(PKG, "libpme.so")

@@ -48,13 +48,6 @@ k_weight_rowsum(const uint8_t* __restrict__ qw, int kb, int32_t* __restrict__ ws
     if (lane == 0) wsum[n] = s;
 }
 
-__global__ void __launch_bounds__(256)
-k_probe_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * 256;
-    for (; i < n16; i += stride) dst[i] = src[i];
-}
-
 }  // namespace
 
 pme_status launch_gemm_generic(const GemmArgs& a) {
@@ -72,14 +65,6 @@ pme_status launch_gemm_generic(const GemmArgs& a) {
 
 pme_status launch_weight_rowsum(const uint8_t* qw, int64_t N, int64_t d_e, int32_t* wsum, hipStream_t s) {
     hipLaunchKernelGGL(k_weight_rowsum, dim3((unsigned)N), dim3(64), 0, s, qw, (int)(d_e / 2), wsum);
-    return hip_status(hipGetLastError());
-}
-
-pme_status launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
-    const size_t n16 = bytes / 16;
-    size_t blocks = (n16 + 255) / 256;
-    if (blocks > 256 * 16) blocks = 256 * 16;
-    hipLaunchKernelGGL(k_probe_copy, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n16);
     return hip_status(hipGetLastError());
 }
 

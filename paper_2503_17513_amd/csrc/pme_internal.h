@@ -54,6 +54,8 @@ pme_status launch_gemm_mfma(const GemmArgs& a);
 pme_status launch_gemm_decode(const GemmArgs& a);
 pme_status launch_weight_rowsum(const uint8_t* qw, int64_t N, int64_t d_e, int32_t* wsum, hipStream_t s);
 pme_status launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+constexpr int kProbeMfmaBlocks = 512;   // workgroups of 256 threads the matrix-core probe launches
+pme_status launch_probe_mfma(int kind, int32_t* out, int iters, hipStream_t s);
 void set_gemm_tile_override(int id);
 void set_rotate_tpw_override(int tpw);
 void set_mxgemm_tile_override(int id);

@@ -1,0 +1,78 @@
+// Measurement probes: kernels of known size that give the measured ceilings the hot-path kernels are
+// priced against next to the published ones, and calibrate the profiler's byte counters.
+//   k_probe_copy  plain streaming copy (HBM read + write).
+//   k_probe_mfma  back-to-back independent matrix-core instructions with nothing else in the loop:
+//                 the rate the matrix pipe sustains at the clock the chip actually holds under that load.
+#include "pme_internal.h"
+
+namespace pme {
+namespace {
+
+typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(8))) int i32x8;
+typedef __attribute__((ext_vector_type(16))) int i32x16;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+
+__global__ void __launch_bounds__(256)
+k_probe_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+    const size_t stride = (size_t)gridDim.x * 256;
+    for (; i < n16; i += stride) dst[i] = src[i];
+}
+
+// Four independent accumulator chains per wave, so that the pipe never waits on a result.
+// KIND 0: v_mfma_i32_32x32x32_i8 (65536 ops each).  KIND 1: v_mfma_scale_f32_32x32x64_f8f6f4 with FP4
+// operands (131072 flops each).  The operands are small integers / small E2M1 codes; sums stay finite.
+template <int KIND>
+__global__ void __launch_bounds__(256) k_probe_mfma(int32_t* __restrict__ out, int iters) {
+    const int t = (int)threadIdx.x;
+    int32_t s = 0;
+    if constexpr (KIND == 0) {
+        const i32x4 a = {0x01010101 * (t & 3), 0x01000100, 0x00010001, 0x01010101};
+        const i32x4 b = {0x01010101, 0x00010001, 0x01000100, 0x01010101 * ((t >> 2) & 1)};
+        i32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+        for (int it = 0; it < iters; ++it) {
+            c0 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c0, 0, 0, 0);
+            c1 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c1, 0, 0, 0);
+            c2 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c2, 0, 0, 0);
+            c3 = __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c3, 0, 0, 0);
+        }
+#pragma unroll
+        for (int e = 0; e < 16; ++e) s += c0[e] + c1[e] + c2[e] + c3[e];
+    } else {
+        // E2M1 codes 0x2 = 1.0, 0x1 = 0.5, 0x0 = 0; scale byte 120 = 2^-7 keeps the sums small
+        const i32x8 a = {0x22222222, 0x11111111 * (t & 1), 0x20202020, 0x02020202, 0, 0, 0, 0};
+        const i32x8 b = {0x12121212, 0x22222222, 0x11111111 * ((t >> 1) & 1), 0x21212121, 0, 0, 0, 0};
+        f32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
+        for (int it = 0; it < iters; ++it) {
+            c0 = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c0, 4, 4, 0, 120, 0, 120);
+            c1 = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c1, 4, 4, 0, 120, 0, 120);
+            c2 = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c2, 4, 4, 0, 120, 0, 120);
+            c3 = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c3, 4, 4, 0, 120, 0, 120);
+        }
+        float f = 0.f;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) f += c0[e] + c1[e] + c2[e] + c3[e];
+        s = (int32_t)__float_as_uint(f);
+    }
+    out[(size_t)blockIdx.x * 256 + t] = s;
+}
+
+}  // namespace
+
+pme_status launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
+    const size_t n16 = bytes / 16;
+    size_t blocks = (n16 + 255) / 256;
+    if (blocks > 256 * 16) blocks = 256 * 16;
+    hipLaunchKernelGGL(k_probe_copy, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n16);
+    return hip_status(hipGetLastError());
+}
+
+pme_status launch_probe_mfma(int kind, int32_t* out, int iters, hipStream_t s) {
+    // 512 workgroups of 4 waves: two waves on every SIMD of the 256 compute units
+    if (kind == 0) hipLaunchKernelGGL(k_probe_mfma<0>, dim3(kProbeMfmaBlocks), dim3(256), 0, s, out, iters);
+    else hipLaunchKernelGGL(k_probe_mfma<1>, dim3(kProbeMfmaBlocks), dim3(256), 0, s, out, iters);
+    return hip_status(hipGetLastError());
+}
+
+}  // namespace pme

@@ -162,6 +162,16 @@ def test_probe_copy_errors():
     assert f(FAKE, FAKE, 0, None) == OK
 
 
+def test_probe_mfma_errors():
+    f = pme.lib().pme_probe_mfma
+    n = 512 * 256
+    assert f(0, None, n, 10, None, None) == NULL
+    assert f(2, FAKE, n, 10, None, None) == DTYPE
+    assert f(0, FAKE, n - 1, 10, None, None) == SHAPE
+    assert f(1, FAKE, n, -1, None, None) == SHAPE
+    assert f(0, FAKE + 2, n, 10, None, None) == ALIGN
+
+
 def test_binding_has_no_fallback():
     # The binding refuses host tensors instead of computing anything itself.
     import torch

@@ -301,6 +301,19 @@ def test_forced_mfma_path_refuses_unsupported_shape():
         pme.w4a4_gemm_i32(q, q)               # d_e = 80 is not a multiple of 128
 
 
+def test_probe_mfma():
+    # every accumulator grows by the same amount per instruction: the checksum is linear in iters
+    out = torch.zeros(512 * 256, dtype=torch.int32, device="cuda")
+    assert pme.probe_mfma(0, out, 10) == 512 * 16 * 10 * 65536.0
+    one = out.clone()
+    assert pme.probe_mfma(0, out, 30) == 512 * 16 * 30 * 65536.0
+    assert one.abs().sum().item() > 0 and torch.equal(out, 3 * one)
+    assert pme.probe_mfma(1, out, 10) == 512 * 16 * 10 * 131072.0
+    f10 = out.view(torch.float32).clone()
+    pme.probe_mfma(1, out, 20)
+    assert f10.abs().sum().item() > 0 and torch.equal(out.view(torch.float32), 2 * f10)
+
+
 def test_probe_copy():
     src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
     dst = torch.zeros_like(src)
