@@ -22,6 +22,9 @@
 //    bf16, transposes through LDS and stores as 16-byte row pieces.
 #include "pme_internal.h"
 
+#include <algorithm>
+#include <type_traits>
+
 namespace pme {
 namespace {
 
@@ -52,8 +55,10 @@ template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_wai
 // 16 bytes per lane from global memory straight into LDS at lds_base + 16 * lane (lds_base wave-uniform).
 // The statement overwrites M0, which the compiler reserves and does not keep values in; no other code in
 // this kernel makes the compiler emit an M0 use.
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+// The source is a wave-uniform 64-bit base (SGPR pair) plus a 32-bit byte offset per lane: no vector
+// arithmetic is needed to move the window along K.
+__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory");
 }
 
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
@@ -85,7 +90,7 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
 
     extern __shared__ __align__(1024) unsigned char smem[];      // NSTAGE stages
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
 
     int tm, tn;
@@ -94,16 +99,18 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
 
     // DMA source of each 16-byte chunk this lane moves: block blk covers tile rows RPB blk .. RPB blk + RPB - 1;
     // lane L writes chunk position L % CPR of row RPB blk + L / CPR, which holds chunk (L % CPR) ^ swz(row).
-    const uint8_t* src[CH];
+    // A 1 KB block lies wholly in the token rows or wholly in the channel rows (BM is a multiple of RPB), so
+    // the operand a DMA slot reads from is wave-uniform; the lane keeps its byte offset within that operand.
+    static_assert(BM % RPB == 0, "DMA blocks do not straddle the operands");
+    uint32_t voff[CH];
     int kcl[CH];          // logical chunk each DMA slot of this lane carries (for the shortened last K step)
 #pragma unroll
     for (int s = 0; s < CH; ++s) {
         const int r = RPB * ((wave + NW * s) % BLKS) + lane / CPR;
         const int kc = (lane % CPR) ^ swz<RB>(r);
         kcl[s] = kc;
-        const uint8_t* base = (r < BM) ? qx + (int64_t)min(m0 + r, T - 1) * kb
-                                       : qw + (int64_t)min(n0 + r - BM, N - 1) * kb;
-        src[s] = base + kc * 16;
+        const int row = (r < BM) ? min(m0 + r, T - 1) : min(n0 + r - BM, N - 1);
+        voff[s] = (uint32_t)row * (uint32_t)kb + (uint32_t)(kc * 16);
     }
     // The tile's scales are fetched now and stay in registers through the K loop, so that the epilogue does
     // not start with a dependent round trip to memory: sx (times 1/256, which removes the 16 x 16 of the
@@ -126,13 +133,18 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     const int KT = (kb + RB - 1) / RB;
     const int tail_chunks = (kb - (KT - 1) * RB) / 16;          // chunks of the last K step
     const int tail_sub = tail_chunks / 2;                       // its sub-steps (64 codes = 2 chunks each)
+    // whole: the K step is a full one, every lane takes part (no predicate, hence no control flow)
+    auto issue_slot = [&](int stage, int kt, int s, auto whole) {
+        const int blk = (wave + NW * s) % BLKS;
+        const uint8_t* base = (blk < BM / RPB ? qx : qw) + (int64_t)kt * RB;
+        if (decltype(whole)::value || kcl[s] < tail_chunks) dma16(base, voff[s], lds0 + stage * STAGE + blk * 1024);
+    };
     auto issue = [&](int stage, int kt) {
-        const int lim = (kt == KT - 1) ? tail_chunks : CPR;
 #pragma unroll
-        for (int s = 0; s < CH; ++s)
-            if (kcl[s] < lim)
-                dma16(src[s] + (int64_t)kt * RB,
-                      __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + ((wave + NW * s) % BLKS) * 1024));
+        for (int s = 0; s < CH; ++s) {
+            if (kt == KT - 1) issue_slot(stage, kt, s, std::false_type{});
+            else issue_slot(stage, kt, s, std::true_type{});
+        }
     };
 
     i32x16 acc[FM][FN];
@@ -185,6 +197,38 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
                 u.bhi[j][e] = (int)(f.b[j][e] & 0xF0F0F0F0u);
             }
     };
+    // The same two steps cut into NPART parts (part c of the fragments' dwords, part c of the matrix
+    // instructions), for the region that also issues the DMA of a later K step: one DMA instruction goes
+    // between consecutive parts, so that the matrix pipe works through part c while the wave is held up
+    // issuing the DMA.
+    constexpr int NPART = CH;
+    constexpr int NITEM = 4 * (FM + FN);          // dwords to unpack per sub-step
+    auto unpack_part = [&](const Frags& f, Unpacked& u, int c) {
+#pragma unroll
+        for (int q = 0; q < NITEM; ++q) {
+            if (q * NPART / NITEM != c) continue;
+            const int fr = q >> 2, e = q & 3;
+            if (fr < FM) {
+                uint32_t w = f.a[fr][e];
+                if (MODE == MODE_ASYM) w ^= 0x88888888u;
+                u.alo[fr][e] = (int)((w & 0x0F0F0F0Fu) << 4);
+                u.ahi[fr][e] = (int)(w & 0xF0F0F0F0u);
+            } else {
+                const uint32_t w = f.b[fr - FM][e];
+                u.blo[fr - FM][e] = (int)((w & 0x0F0F0F0Fu) << 4);
+                u.bhi[fr - FM][e] = (int)(w & 0xF0F0F0F0u);
+            }
+        }
+    };
+    auto mfma_part = [&](const Unpacked& u, int c) {
+#pragma unroll
+        for (int m = 0; m < 2 * FM * FN; ++m) {
+            if (m * NPART / (2 * FM * FN) != c) continue;
+            const int i = m / (2 * FN), j = (m >> 1) % FN;
+            if ((m & 1) == 0) acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.blo[j], u.alo[i], acc[i][j], 0, 0, 0);
+            else acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(u.bhi[j], u.ahi[i], acc[i][j], 0, 0, 0);
+        }
+    };
     auto mfma_all = [&](const Unpacked& u) {
 #pragma unroll
         for (int i = 0; i < FM; ++i)
@@ -226,25 +270,53 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     load_frags(raw[1], smem, 1);
     unpack(raw[0], unp[0]);
     int cur = 0;                    // stage of K step kt
-    for (int kt = 0; kt + 1 < KT; ++kt) {
-        const int nxt = (cur == NSTAGE - 1) ? 0 : cur + 1;
-        const unsigned char* scur = smem + cur * STAGE;
-        const unsigned char* snxt = smem + nxt * STAGE;
+    // K steps [k0, k1); whole: every K step whose DMA they issue is a full one
+    auto k_steps = [&](int k0, int k1, auto whole) {
+        for (int kt = k0; kt < k1; ++kt) {
+            const int nxt = (cur == NSTAGE - 1) ? 0 : cur + 1;
+            const unsigned char* scur = smem + cur * STAGE;
+            const unsigned char* snxt = smem + nxt * STAGE;
 #pragma unroll
-        for (int s = 0; s < NSUB; ++s) {
-            if (s == NSUB - 2) {
-                wait_vm<(NSTAGE - 2) * CH>();
-                lds_barrier();      // stage nxt has landed for every wave; every wave has left stage cur
-                issue(cur, min(kt + NSTAGE, KT - 1));
+            for (int s = 0; s < NSUB; ++s) {
+                if (s == NSUB - 2) {
+                    wait_vm<(NSTAGE - 2) * CH>();
+                    lds_barrier();      // stage nxt has landed for every wave; every wave has left stage cur
+                }
+                if (s + 2 < NSUB) load_frags(raw[s & 1], scur, s + 2);
+                else load_frags(raw[s & 1], snxt, s + 2 - NSUB);
+                if (s != NSUB - 2) {
+                    unpack(raw[(s + 1) & 1], unp[(s + 1) & 1]);
+                    mfma_all(unp[s & 1]);
+                    interleave(true);
+                } else {
+                    // the region after the barrier also refills stage cur with K step kt + NSTAGE, one DMA
+                    // instruction after each part of the matrix work
+                    const int ktn = min(kt + NSTAGE, KT - 1);
+#pragma unroll
+                    for (int c = 0; c < NPART; ++c) {
+                        unpack_part(raw[(s + 1) & 1], unp[(s + 1) & 1], c);
+                        mfma_part(unp[s & 1], c);
+                        if (c == 0) __builtin_amdgcn_sched_group_barrier(0x100, FM + FN, 0);
+                        constexpr int MPP = (NMFMA + NPART - 1) / NPART;       // most matrix instructions of a part
+#pragma unroll
+                        for (int m = 0; m < MPP; ++m) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        issue_slot(cur, ktn, c, whole);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
             }
-            if (s + 2 < NSUB) load_frags(raw[s & 1], scur, s + 2);
-            else load_frags(raw[s & 1], snxt, s + 2 - NSUB);
-            unpack(raw[(s + 1) & 1], unp[(s + 1) & 1]);
-            mfma_all(unp[s & 1]);
-            interleave(true);
+            cur = nxt;
         }
-        cur = nxt;
-    }
+    };
+    // The steps that fetch the shortened last K step (a lane predicate, hence control flow between the
+    // matrix instructions) are kept apart from the bulk, whose DMA is unconditional.
+    const int k_whole = (tail_chunks == CPR) ? KT - 1 : max(0, KT - 1 - NSTAGE);
+    k_steps(0, k_whole, std::true_type{});
+    k_steps(k_whole, KT - 1, std::false_type{});
     {
         const unsigned char* scur = smem + cur * STAGE;
 #pragma unroll
@@ -346,6 +418,7 @@ template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE>
 pme_status launch_tile(const GemmArgs& a) {
     const int kb = (int)(a.d_e / 2);
     if (kb % 64) return PME_ERR_UNSUPPORTED_PATH;      // whole sub-steps; the last K step may be half as long
+    if ((int64_t)std::max(a.T, a.N) * kb >= (int64_t(1) << 32)) return PME_ERR_UNSUPPORTED_PATH;   // 32-bit DMA offsets
     const int tiles_m = (int)((a.T + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WGM * WGN);
     const size_t lds = (size_t)NSTAGE * (BM + BN) * RB;
