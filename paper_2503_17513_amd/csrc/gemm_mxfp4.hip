@@ -9,6 +9,10 @@
 // Accumulation is fp32 in the matrix core; the epilogue rounds to bf16 and stores 16-byte row pieces.
 #include "pme_internal.h"
 
+#include <algorithm>
+#include <type_traits>
+#include <utility>
+
 namespace pme {
 namespace {
 
@@ -28,11 +32,12 @@ __device__ __forceinline__ void lds_barrier() { asm volatile("s_waitcnt lgkmcnt(
 template <int N> __device__ __forceinline__ void wait_vm() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory"); }
 // DMA of 16 / 4 bytes per lane into LDS at lds_base + 16 / 4 * lane (lds_base wave-uniform).  Overwrites M0,
 // which the compiler does not keep values in; nothing else in this kernel makes the compiler use M0.
-__device__ __forceinline__ void dma16(const void* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+// The source is a wave-uniform 64-bit base (SGPR pair) plus a 32-bit byte offset per lane.
+__device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory");
 }
-__device__ __forceinline__ void dma4(const void* gptr, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dword %0, off" ::"v"(gptr), "s"(lds_base) : "memory");
+__device__ __forceinline__ void dma4(const void* sbase, uint32_t voff, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1" ::"v"(voff), "s"(sbase), "s"(lds_base) : "memory");
 }
 __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     const bf16x2 p = __builtin_convertvector(f32x2{a, b}, bf16x2);
@@ -62,39 +67,48 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
 
     extern __shared__ __align__(1024) unsigned char smem[];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WGN, wn = wave % WGN;
     int tm, tn;
     xcd_tile((int)blockIdx.x, tiles_m, tiles_n, xcd_gm, tm, tn);     // compact tile block per XCD
     const int m0 = tm * BM, n0 = tn * BN;
 
-    const uint8_t* src[CH];
+    // A DMA block lies wholly in the token rows or wholly in the channel rows, so the operand a slot reads
+    // from is wave-uniform; the lane keeps its byte offset within that operand.
+    static_assert(BM % RPB == 0 && BM % 64 == 0, "DMA blocks do not straddle the operands");
+    uint32_t voff[CH];
 #pragma unroll
     for (int s = 0; s < CH; ++s) {
         const int r = RPB * ((wave + NW * s) % BLKS) + lane / CPR;
         const int kc = (lane % CPR) ^ swz<RB>(r);
-        const uint8_t* base = (r < BM) ? qx + (int64_t)min(m0 + r, T - 1) * kb : qw + (int64_t)min(n0 + r - BM, N - 1) * kb;
-        src[s] = base + kc * 16;
+        const int row = (r < BM) ? min(m0 + r, T - 1) : min(n0 + r - BM, N - 1);
+        voff[s] = (uint32_t)row * (uint32_t)kb + (uint32_t)(kc * 16);
     }
     // scale bytes: block sb = plane * (ROWS / 64) + rows-of-64 index; lane = row within the 64
-    const uint8_t* ssrc[SCH];
+    uint32_t svoff[SCH];
 #pragma unroll
     for (int s = 0; s < SCH; ++s) {
         const int sb = (wave + NW * s) % SBLKS;
         const int plane = sb / (ROWS / 64), r = 64 * (sb % (ROWS / 64)) + lane;
-        const uint8_t* base = (r < BM) ? ex + (int64_t)min(m0 + r, T - 1) * eb : ew + (int64_t)min(n0 + r - BM, N - 1) * eb;
-        ssrc[s] = base + 4 * plane;
+        const int row = (r < BM) ? min(m0 + r, T - 1) : min(n0 + r - BM, N - 1);
+        svoff[s] = (uint32_t)row * (uint32_t)eb + (uint32_t)(4 * plane);
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(PME_AS3 unsigned char*)smem;
+    // DMA slot q of this wave for K step kt: slots 0 .. CH - 1 move codes, CH .. CH + SCH - 1 scale bytes
+    constexpr int NSLOT = CH + SCH;
+    auto issue_slot = [&](int stage, int kt, int q) {
+        if (q < CH) {
+            const int blk = (wave + NW * q) % BLKS;
+            dma16((blk < BM / RPB ? qx : qw) + (int64_t)kt * RB, voff[q], lds0 + stage * STAGE + blk * 1024);
+        } else {
+            const int sb = (wave + NW * (q - CH)) % SBLKS;
+            dma4((64 * (sb % (ROWS / 64)) < BM ? ex : ew) + (int64_t)kt * (RB / 16), svoff[q - CH],
+                 lds0 + stage * STAGE + CODE_BYTES + sb * 256);
+        }
+    };
     auto issue = [&](int stage, int kt) {
 #pragma unroll
-        for (int s = 0; s < CH; ++s)
-            dma16(src[s] + (int64_t)kt * RB,
-                  __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + ((wave + NW * s) % BLKS) * 1024));
-#pragma unroll
-        for (int s = 0; s < SCH; ++s)
-            dma4(ssrc[s] + (int64_t)kt * (RB / 16),
-                 __builtin_amdgcn_readfirstlane(lds0 + stage * STAGE + CODE_BYTES + ((wave + NW * s) % SBLKS) * 256));
+        for (int q = 0; q < NSLOT; ++q) issue_slot(stage, kt, q);
     };
 
     f32x16 acc[FM][FN];
@@ -135,6 +149,13 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
             f.sb[j] = *reinterpret_cast<const uint32_t*>(stage + bsoff[j] + (s >> 1) * ROWS * 4) >> sh;
         }
     };
+    auto mfma_one = [&](const Frags& f, auto mc) {            // instruction m of the FM x FN of a sub-step
+        constexpr int i = decltype(mc)::value / FN, j = decltype(mc)::value % FN;
+        const i32x8 xa = {(int)f.a[i][0], (int)f.a[i][1], (int)f.a[i][2], (int)f.a[i][3], 0, 0, 0, 0};
+        const i32x8 wb = {(int)f.b[j][0], (int)f.b[j][1], (int)f.b[j][2], (int)f.b[j][3], 0, 0, 0, 0};
+        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wb, xa, acc[i][j], 4, 4, 0, (int)f.sb[j], 0,
+                                                                    (int)f.sa[i]);
+    };
     auto mfma_all = [&](const Frags& f) {
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
@@ -169,12 +190,27 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
             if (s == NSUB - 1) {
                 wait_vm<(NSTAGE - 2) * (CH + SCH)>();
                 lds_barrier();
-                issue(cur, min(kt + NSTAGE, KT - 1));
                 load_frags(raw[(s + 1) & 1], snxt, 0);
+                // refill the stage just left with K step kt + NSTAGE: the DMA instructions go between the
+                // matrix instructions, which keep the pipe busy while the wave is held up issuing them
+                const int ktn = min(kt + NSTAGE, KT - 1);
+                constexpr int NM = FM * FN;
+                constexpr int NP = NM < NSLOT ? NM : NSLOT;
+                static_for<NP>([&](auto pc) {
+                    constexpr int c = decltype(pc)::value;
+                    static_for<NM>([&](auto mc) {
+                        if constexpr (decltype(mc)::value * NP / NM == c) mfma_one(raw[s & 1], mc);
+                    });
+                    __builtin_amdgcn_sched_barrier(0);
+                    static_for<NSLOT>([&](auto qc) {
+                        if constexpr (decltype(qc)::value * NP / NSLOT == c) issue_slot(cur, ktn, decltype(qc)::value);
+                    });
+                    __builtin_amdgcn_sched_barrier(0);
+                });
             } else {
                 load_frags(raw[(s + 1) & 1], scur, s + 1);
+                mfma_all(raw[s & 1]);
             }
-            mfma_all(raw[s & 1]);
         }
         cur = nxt;
     }
@@ -228,6 +264,7 @@ template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE>
 pme_status launch_tile(const MxGemmArgs& a) {
     const int kb = (int)(a.d_e / 2), eb = (int)(a.d_e / 32);
     if (kb % RB) return PME_ERR_UNSUPPORTED_PATH;
+    if ((int64_t)std::max(a.T, a.N) * kb >= (int64_t(1) << 32)) return PME_ERR_UNSUPPORTED_PATH;   // 32-bit DMA offsets
     const int tiles_m = (int)((a.T + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WGM * WGN);
     const size_t lds = (size_t)NSTAGE * ((BM + BN) * RB + (BM + BN) * 4 * (RB / 64));

@@ -1,6 +1,9 @@
 // Internal declarations shared by the translation units of libpme (not installed).
 #pragma once
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
+#include <utility>
 #include <stdint.h>
 #include "../../include/pme.h"
 
@@ -59,6 +62,14 @@ pme_status launch_probe_mfma(int kind, int32_t* out, int iters, hipStream_t s);
 void set_gemm_tile_override(int id);
 void set_rotate_tpw_override(int tpw);
 void set_mxgemm_tile_override(int id);
+
+// Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{}).
+template <class F, int... I> __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {
+    (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F> __device__ __forceinline__ void static_for(F&& f) {
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
 
 inline pme_status hip_status(hipError_t e) { return e == hipSuccess ? PME_OK : PME_ERR_HIP; }
 
