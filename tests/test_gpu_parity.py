@@ -186,6 +186,31 @@ def test_gemm_every_tile_configuration(tile, d_e):
     check_bf16(y, oracle.dequant_bf16(acc_ref, sx, sw))
 
 
+@pytest.mark.parametrize("tm,tn", [(8, 1), (1, 8), (4, 2), (2, 4), (16, 16), (3, 5), (24, 8)])
+def test_gemm_tile_map_is_a_bijection(tm, tn):
+    # The workgroup -> tile map hands each XCD a block of tiles; the split (8x1, 4x2, 2x4, 1x8 XCDs, or none
+    # when the tile counts do not divide) depends on the tile grid.  Every output must be written exactly
+    # once and exactly: 64 x 64 and 64 x 128 tiles, one short K step.  A block of the output's size is
+    # poisoned and released first, so that the allocator does not hand back an earlier, correct result.
+    rng = np.random.default_rng(100 * tm + tn)
+    T, N, d_e = 64 * tm, 64 * tn, 128
+    q = rng.integers(-7, 8, size=(T, d_e), dtype=np.int8)
+    qw = rng.integers(-8, 8, size=(N, d_e), dtype=np.int8)
+    acc_ref = oracle.int_gemm(q, qw)
+    qd = torch.from_numpy(oracle.pack_int4(q)).cuda()
+    wd = torch.from_numpy(oracle.pack_int4(qw)).cuda()
+    pme.set_path(MFMA)
+    for tile in (7, 6):
+        poison = torch.full((T, N), 0x7FFFFFFF, dtype=torch.int32, device="cuda")
+        del poison
+        pme.set_gemm_tile(tile)
+        try:
+            acc = pme.w4a4_gemm_i32(qd, wd).cpu().numpy()
+        finally:
+            pme.set_gemm_tile(0)
+        assert np.array_equal(acc, acc_ref), f"tile {tile}: {np.count_nonzero(acc != acc_ref)} accumulators differ"
+
+
 @pytest.mark.parametrize("T", (150, 8))
 @pytest.mark.parametrize("path", (GENERIC, MFMA))
 def test_gemm_asymmetric(path, T):
