@@ -130,6 +130,8 @@ GEMM_CASES = [
     ("decode_16_tokens_ragged_n", 16, 100, 384, (GENERIC, MFMA)),
     ("decode_one_chunk", 3, 40, 128, (GENERIC, MFMA)),
     ("decode_one_token_long_k", 1, 520, 15360, (GENERIC, MFMA)),
+    ("decode_five_tokens_odd_chunks_ragged_n", 5, 36, 640, (GENERIC, MFMA)),
+    ("decode_nine_tokens", 9, 50, 640, (GENERIC, MFMA)),
     ("seventeen_tokens_use_the_tiled_kernel", 17, 64, 256, (GENERIC, MFMA)),
 ]
 
