@@ -423,10 +423,11 @@ pme_status launch_tile(const GemmArgs& a) {
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WGM * WGN);
     const size_t lds = (size_t)NSTAGE * (BM + BN) * RB;
     if (lds > 64 * 1024) {
-        hipError_t e0 = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_BF16>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipError_t e1 = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_ASYM>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        hipError_t e2 = hipFuncSetAttribute((const void*)k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_I32>, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e0 != hipSuccess || e1 != hipSuccess || e2 != hipSuccess) return PME_ERR_HIP;
+        static std::atomic<uint32_t> done[3];
+        if (allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_BF16>, (int)lds, done[0]) != PME_OK ||
+            allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_ASYM>, (int)lds, done[1]) != PME_OK ||
+            allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_I32>, (int)lds, done[2]) != PME_OK)
+            return PME_ERR_HIP;
     }
     // 16-byte output pieces need 8-element alignment of N, the pitch and the base
     const int vec = (a.N % 8 == 0 && a.ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0) ? 1 : 0;

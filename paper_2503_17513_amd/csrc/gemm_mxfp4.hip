@@ -269,9 +269,8 @@ pme_status launch_tile(const MxGemmArgs& a) {
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WGM * WGN);
     const size_t lds = (size_t)NSTAGE * ((BM + BN) * RB + (BM + BN) * 4 * (RB / 64));
     auto kern = k_mxgemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE>;
-    if (lds > 64 * 1024 &&
-        hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-        return PME_ERR_HIP;
+    static std::atomic<uint32_t> done;
+    if (lds > 64 * 1024 && allow_dynamic_lds(kern, (int)lds, done) != PME_OK) return PME_ERR_HIP;
     const int vec = (a.N % 8 == 0 && a.ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0) ? 1 : 0;
     hipLaunchKernelGGL(kern, grid, block, lds, a.stream, a.qx, a.ex, a.qw, a.ew, (int)a.T, (int)a.N, kb, eb,
                        static_cast<uint16_t*>(a.y), a.ldy, tiles_m, tiles_n, xcd_grid_m(tiles_m, tiles_n, BM, BN), vec);

@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 
+#include <atomic>
 #include <type_traits>
 #include <utility>
 #include <stdint.h>
@@ -62,6 +63,19 @@ pme_status launch_probe_mfma(int kind, int32_t* out, int iters, hipStream_t s);
 void set_gemm_tile_override(int id);
 void set_rotate_tpw_override(int tpw);
 void set_mxgemm_tile_override(int id);
+
+// Lets `kern` be launched with up to `bytes` of dynamic LDS.  The attribute is set once per kernel and
+// device (`done` holds one bit per device and belongs to the kernel's launcher), not on every launch.
+template <class K> inline pme_status allow_dynamic_lds(K kern, int bytes, std::atomic<uint32_t>& done) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return PME_ERR_HIP;
+    const uint32_t bit = 1u << (dev & 31);
+    if (done.load(std::memory_order_acquire) & bit) return PME_OK;
+    if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, bytes) != hipSuccess)
+        return PME_ERR_HIP;
+    done.fetch_or(bit, std::memory_order_release);
+    return PME_OK;
+}
 
 // Compile-time loop: f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{}).
 template <class F, int... I> __device__ __forceinline__ void static_for_impl(F&& f, std::integer_sequence<int, I...>) {

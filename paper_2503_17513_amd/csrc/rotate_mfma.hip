@@ -574,16 +574,17 @@ pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     using L = Layout<KLOG2>;
     constexpr int NS = F32IN ? 3 : 1;
     const size_t lds = (size_t)NS * ks * L::MT * 1024 + (size_t)nwaves * TPW * ks * 1024;
-    if (lds + 256 > 160 * 1024 || nwaves > max_waves<KLOG2, TPW>()) return PME_ERR_UNSUPPORTED_PATH;
+    // 160 KB per workgroup, less the kernel's static LDS rounded up to the dynamic part's 1 KB alignment
+    constexpr size_t kMaxDynLds = 160 * 1024 - 1024;
+    if (lds > kMaxDynLds || nwaves > max_waves<KLOG2, TPW>()) return PME_ERR_UNSUPPORTED_PATH;
     const int rows = (int)((a.d + L::NC - 1) >> KLOG2);
     pme_status st = PME_OK;
     const int slot = table_slot(a.b, rows, a.stream, &st);
     if (slot < 0) return st;
     auto kern = k_rotate_mfma<KLOG2, TPW, F32IN, OUT>;
-    if (lds > 48 * 1024) {
-        if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess)
-            return PME_ERR_HIP;
-    }
+    // the same kernel runs with different LDS sizes (they follow the shape): allow the largest one accepted above
+    static std::atomic<uint32_t> done;
+    if (lds > 48 * 1024 && allow_dynamic_lds(kern, (int)kMaxDynLds, done) != PME_OK) return PME_ERR_HIP;
     // Persistent grid: as many workgroups as fit on the 256 compute units at once (LDS, and about 12
     // waves per compute unit at this register use), preferring a count that divides the tokens evenly.
     int occ = (int)((160 * 1024) / (lds + 1024));
