@@ -236,7 +236,11 @@ template <int KLOG2, int TPW> constexpr int max_waves() { return (TPW == 1 && KL
 
 enum { OUT_SYM = 0, OUT_ASYM = 1, OUT_XHAT = 2, OUT_MXFP4 = 3 };   // int4 symmetric / asymmetric codes, fp32 values, MXFP4
 
-template <int KLOG2, int TPW, bool F32IN, int OUT>
+// MULTI: a token fits one wave (all its tiles are this wave's TPW tiles), and every wave of the workgroup
+// rotates tokens of its own, in a token buffer of its own; only the B fragments are shared.  Compared
+// with one-wave workgroups this loads the fragments once per several tokens and hands the dispatcher
+// fewer workgroups, which is what counts at small 2^k, where a token is only a few KB.
+template <int KLOG2, int TPW, bool F32IN, int OUT, bool MULTI = false>
 __global__ void __launch_bounds__((64 * max_waves<KLOG2, TPW>()))
 k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, int b, int ks_count, int slot,
               double gamma, uint8_t* __restrict__ qx, float* __restrict__ sx, int32_t* __restrict__ zx,
@@ -249,11 +253,16 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
     extern __shared__ __align__(1024) unsigned char smem[];   // NS token planes, then the B fragments
     __shared__ float red[2 * kMaxWaves];
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nwaves = blockDim.x >> 6, nthreads = blockDim.x;
+    static_assert(!(MULTI && F32IN), "the multi-token variant takes bf16 input");
+    const int lane = threadIdx.x & 63, wave_hw = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), nwaves_hw = blockDim.x >> 6;
+    // the waves that share a token, and this thread's place among them
+    const int wave = MULTI ? 0 : wave_hw, nwaves = MULTI ? 1 : nwaves_hw;
+    const int tid = MULTI ? lane : (int)threadIdx.x, nthreads = MULTI ? 64 : (int)blockDim.x;
     const int l15 = lane & 15, g = lane >> 4;
     const int rows_k = 32 * ks_count;                 // rows of the K-padded operand
-    unsigned char* bsm = smem + NS * plane_bytes + (size_t)wave * TPW * ks_count * 1024;   // this wave's B fragments
+    unsigned char* tsm = smem + (MULTI ? (size_t)wave_hw * NS * plane_bytes : 0);          // this token's planes
+    // B fragments: this wave's tiles; MULTI: all tiles, shared by the workgroup's waves
+    unsigned char* bsm = smem + (size_t)(MULTI ? nwaves_hw : 1) * NS * plane_bytes + (size_t)wave * TPW * ks_count * 1024;
 
     const int real_groups = (((d + NC - 1) >> KLOG2) + 3) >> 2;        // 4-row groups holding real inputs
     const int nchunks = real_groups * MT * 8;
@@ -264,10 +273,10 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
         for (int p = first + tid; p < total; p += nthreads) {
             const int blk = p >> 3, r = p & 7;
             const int a = 4 * (blk / MT) + (r >> 1), c = 16 * (blk % MT) + 8 * (r & 1);
-            if (a * NC + c >= d) *reinterpret_cast<u32x4*>(smem + (size_t)p * 16) = u32x4{0u, 0u, 0u, 0u};
+            if (a * NC + c >= d) *reinterpret_cast<u32x4*>(tsm + (size_t)p * 16) = u32x4{0u, 0u, 0u, 0u};
         }
     }
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(PME_AS3 unsigned char*)smem;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(PME_AS3 unsigned char*)tsm;
 
     // bf16 token: HBM -> LDS by DMA, 16 bytes per lane, laid out for the transposing reads
     // Chunk p = 64 (wave + nwaves s) + lane of the LDS image holds the 8 inputs (a, c .. c + 7) with, for
@@ -310,7 +319,7 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
                 h2[e] = split_hi(r2, r3);
             }
             const int ks = ag >> 2, gg = ag & 3, mt = c >> 4;
-            unsigned char* dst = smem + ((size_t)((ks * MT + mt) * 64 + (c & 15) + 16 * gg)) * 16;
+            unsigned char* dst = tsm + ((size_t)((ks * MT + mt) * 64 + (c & 15) + 16 * gg)) * 16;
             u32x4 p0, p1, p2;
 #pragma unroll
             for (int p = 0; p < 4; ++p) {
@@ -324,29 +333,45 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
         }
     };
 
-    int64_t t = blockIdx.x;
+    const int64_t t_step = MULTI ? (int64_t)gridDim.x * nwaves_hw : gridDim.x;
+    int64_t t = MULTI ? (int64_t)blockIdx.x * nwaves_hw + wave_hw : blockIdx.x;
     if constexpr (!F32IN) {
         if (t < T) load_token_dma(t);       // in flight while the B fragments are fetched
     }
     // ---- once per workgroup: B fragments of P into LDS
+    if constexpr (MULTI) {
+        for (int f = wave_hw; f < TPW * ks_count; f += nwaves_hw) {       // fragment f = ti ks_count + ks
+            const int tile = min(f / ks_count, kMaxTiles - 1);
+            *reinterpret_cast<u32x4*>(bsm + ((size_t)f * 64 + lane) * 16) = g_ptable[slot][tile * kMaxKs + f % ks_count][lane];
+        }
+        lds_barrier();                      // the only workgroup barrier: every wave passes it exactly once
+    } else {
 #pragma unroll
-    for (int ti = 0; ti < TPW; ++ti) {
-        const int tile = min(wave * TPW + ti, kMaxTiles - 1);
-        for (int ks = 0; ks < ks_count; ++ks)
-            *reinterpret_cast<u32x4*>(bsm + ((size_t)(ti * ks_count + ks) * 64 + lane) * 16) = g_ptable[slot][tile * kMaxKs + ks][lane];
+        for (int ti = 0; ti < TPW; ++ti) {
+            const int tile = min(wave * TPW + ti, kMaxTiles - 1);
+            for (int ks = 0; ks < ks_count; ++ks)
+                *reinterpret_cast<u32x4*>(bsm + ((size_t)(ti * ks_count + ks) * 64 + lane) * 16) = g_ptable[slot][tile * kMaxKs + ks][lane];
+        }
     }
+    // Synchronisation among the waves that share a token: a barrier, or for a single wave only a wait for
+    // its own LDS traffic (waves of a multi-token workgroup run different numbers of tokens, so they must
+    // not meet at barriers inside the token loop).
+    auto token_sync = [&]() {
+        if constexpr (MULTI) asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        else lds_barrier();
+    };
     const int l4 = (lane >> 4) & 1, l5 = lane >> 5;
     const int c0 = run_start<KLOG2>(l4, l5);
     const float g7 = (float)(gamma / 7.0);
 
-    for (; t < T; t += gridDim.x) {
+    for (; t < T; t += t_step) {
         if constexpr (F32IN) {
             lds_barrier();                  // every wave has finished reading the previous token
             load_token_f32(t);
         } else {
             wait_all_vm();                  // this wave's part of the token (and its earlier stores) has landed
         }
-        lds_barrier();
+        token_sync();
 
         // ---- base block on the matrix cores: Z^T[c][a'] = sum_a X~[a][c] P[a][a']
         f32x4 acc[TPW][MT];
@@ -361,7 +386,7 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
                 if constexpr (!F32IN) {
                     // two transposing reads: lane (g, j = lane % 16) addresses 8 bytes of row 32 ks + 8 g + 4 h + j / 4
                     // and receives rows 32 ks + 8 g + 4 h + (0..3) of column 16 mt + j.
-                    const unsigned char* p0 = smem + ((size_t)((8 * ks + 2 * g) * MT + mt)) * 128 + 8 * l15;
+                    const unsigned char* p0 = tsm + ((size_t)((8 * ks + 2 * g) * MT + mt)) * 128 + 8 * l15;
                     const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 PME_AS3*)p0);
                     const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((s16x4 PME_AS3*)(p0 + MT * 128));
                     typedef __attribute__((ext_vector_type(8))) short s16x8;
@@ -375,7 +400,7 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
 #pragma unroll
                     for (int sp = 0; sp < NS; ++sp) {
                         const u32x4 raw = *reinterpret_cast<const u32x4*>(
-                            smem + (size_t)sp * plane_bytes + ((size_t)((ks * MT + mt) * 64 + lane)) * 16);
+                            tsm + (size_t)sp * plane_bytes + ((size_t)((ks * MT + mt) * 64 + lane)) * 16);
                         const bf16x8 af = __builtin_bit_cast(bf16x8, raw);
 #pragma unroll
                         for (int ti = 0; ti < TPW; ++ti)
@@ -390,8 +415,8 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
 
         if constexpr (!F32IN) {
             // every wave has read the token out of LDS: refill the buffer with the next token now
-            lds_barrier();
-            if (t + gridDim.x < T) load_token_dma(t + gridDim.x);
+            token_sync();
+            if (t + t_step < T) load_token_dma(t + t_step);
         }
 
         // ---- FWHT along c, in registers
@@ -597,6 +622,38 @@ pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     return hip_status(hipGetLastError());
 }
 
+// Multi-token workgroups of kMultiWaves waves (bf16 input, a token per wave).
+constexpr int kMultiWaves = 4;
+template <int KLOG2, int TPW, int OUT>
+pme_status launch_multi_out(const RotateArgs& a, int ks) {
+    using L = Layout<KLOG2>;
+    const size_t lds = (size_t)kMultiWaves * ks * L::MT * 1024 + (size_t)TPW * ks * 1024;
+    constexpr size_t kMaxDynLds = 160 * 1024 - 1024;
+    if (lds > kMaxDynLds) return PME_ERR_UNSUPPORTED_PATH;
+    const int rows = (int)((a.d + L::NC - 1) >> KLOG2);
+    pme_status st = PME_OK;
+    const int slot = table_slot(a.b, rows, a.stream, &st);
+    if (slot < 0) return st;
+    auto kern = k_rotate_mfma<KLOG2, TPW, false, OUT, true>;
+    static std::atomic<uint32_t> done;
+    if (lds > 48 * 1024 && allow_dynamic_lds(kern, (int)kMaxDynLds, done) != PME_OK) return PME_ERR_HIP;
+    int occ = (int)((160 * 1024) / (lds + 1024));
+    occ = std::max(1, std::min(occ, 12 / kMultiWaves));
+    const int64_t groups = (a.T + kMultiWaves - 1) / kMultiWaves;
+    const unsigned grid = (unsigned)std::min<int64_t>(groups, 256 * (int64_t)occ);
+    const double gamma = 1.0 / sqrt((double)a.d_e);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * kMultiWaves), lds, a.stream, a.x, a.ldx, (int)a.T, (int)a.d,
+                       (int)a.d_e, a.b, ks, slot, gamma, a.qx, a.sx, a.zx, a.ex, a.xhat);
+    return hip_status(hipGetLastError());
+}
+template <int KLOG2, int TPW>
+pme_status launch_multi(const RotateArgs& a, int ks) {
+    if (a.xhat) return launch_multi_out<KLOG2, TPW, OUT_XHAT>(a, ks);
+    if (a.ex) return launch_multi_out<KLOG2, TPW, OUT_MXFP4>(a, ks);
+    if (a.zx) return launch_multi_out<KLOG2, TPW, OUT_ASYM>(a, ks);
+    return launch_multi_out<KLOG2, TPW, OUT_SYM>(a, ks);
+}
+
 template <int KLOG2, int TPW, bool F32IN>
 pme_status launch_one(const RotateArgs& a, int ks, int nwaves) {
     if (a.xhat) return launch_out<KLOG2, TPW, F32IN, OUT_XHAT>(a, ks, nwaves);
@@ -606,6 +663,7 @@ pme_status launch_one(const RotateArgs& a, int ks, int nwaves) {
 }
 
 int g_tpw_override = 0;
+int g_multi_override = -1;     // experiments: 0 / 1 force the multi-token variant off / on where it applies
 
 }  // namespace
 
@@ -637,6 +695,9 @@ pme_status launch_rotate_mfma(const RotateArgs& a) {
     if (g_tpw_override > 0) tpw = g_tpw_override;
     const int nwaves = (nt + tpw - 1) / tpw;
     if (nwaves > kMaxWaves) return PME_ERR_UNSUPPORTED_PATH;
+    // 2^k = 32 with a block of at most 80: the token is one wave's work and only a few KB
+    const bool multi = g_multi_override >= 0 ? g_multi_override == 1 : a.T >= 1024;
+    if (!f32 && a.k == 5 && tpw == 5 && nwaves == 1 && multi) return launch_multi<5, 5>(a, ks);
 #define PME_ROT(K, TP)                                                             \
     if (a.k == K && tpw == TP)                                                     \
         return f32 ? launch_one<K, TP, true>(a, ks, nwaves) : launch_one<K, TP, false>(a, ks, nwaves);

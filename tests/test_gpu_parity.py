@@ -48,6 +48,11 @@ ROTATE_CASES = [
     ("b20_k9", 3, 8192, 10240, "bf16", (GENERIC, MFMA)),
     ("b12_k10", 2, 8192, 12288, "bf16", (GENERIC,)),
     ("single_token", 1, 2048, 2176, "bf16", (GENERIC, MFMA)),
+    # 1024 tokens or more at 2^k = 32: workgroups whose waves each rotate tokens of their own (token counts
+    # that do not divide by the waves of a workgroup, one- and five-tile blocks, ragged d)
+    ("b68_k5_token_per_wave", 1030, 2048, 2176, "bf16", (MFMA,)),
+    ("b20_k5_token_per_wave", 1027, 600, 640, "bf16", (MFMA,)),
+    ("b72_k5_token_per_wave_ragged_d", 1025, 2104, 2304, "bf16", (MFMA,)),
 ]
 
 
@@ -94,7 +99,8 @@ def test_rotate_strided_rows(path):
 
 
 ASYM_CASES = [("tiny", 16, 64, 80, "f32", (GENERIC,)), ("b68_k5", 9, 2048, 2176, "bf16", (GENERIC, MFMA)),
-              ("b60_k8", 4, 14336, 15360, "bf16", (GENERIC, MFMA))]
+              ("b60_k8", 4, 14336, 15360, "bf16", (GENERIC, MFMA)),
+              ("b68_k5_token_per_wave", 1026, 2048, 2176, "bf16", (MFMA,))]
 
 
 @pytest.mark.parametrize("name,T,d,d_e,in_dtype,paths", ASYM_CASES, ids=[c[0] for c in ASYM_CASES])
