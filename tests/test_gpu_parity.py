@@ -334,6 +334,30 @@ def test_forced_mfma_path_refuses_unsupported_shape():
         pme.w4a4_gemm_i32(q, q)               # d_e = 80 is not a multiple of 128
 
 
+def test_layer_in_a_hip_graph_replays_identically():
+    # the library only enqueues kernels (no memset nodes, no allocation, no synchronisation once a shape is
+    # warm), so a captured layer call must give the eager result on every replay, with eager work between
+    wl = make_workload(custom_spec(300, 2048, 2176, 520, seed=5))
+    x = torch.from_numpy(wl.x).to(torch.bfloat16).cuda()
+    qw = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+    sw = torch.from_numpy(wl.sw).cuda()
+    y_eager = pme.expanded_linear(x, 2176, qw, sw).clone()           # also warms the shape
+    ws = torch.empty((pme.workspace_bytes(300, 2048, 2176, 520),), dtype=torch.uint8, device="cuda")
+    y = torch.zeros_like(y_eager)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=side):
+        pme.expanded_linear(x, 2176, qw, sw, y, ws)
+    for rep in range(4):
+        y.fill_(float("nan"))                                        # eager work on the outputs between replays
+        ws.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), y_eager.view(torch.int16)), f"replay {rep} differs from the eager result"
+
+
 def test_probe_mfma():
     # every accumulator grows by the same amount per instruction: the checksum is linear in iters
     out = torch.zeros(512 * 256, dtype=torch.int32, device="cuda")
