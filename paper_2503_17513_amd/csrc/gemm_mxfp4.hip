@@ -135,39 +135,43 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
     }
     struct Frags { u32x4 a[FM], b[FN]; uint32_t sa[FM], sb[FN]; };
     // sub-step s: codes of block 2 s + fk of the row (chunk position (2 s + fk) ^ swz), and its scale: byte
-    // (2 s + fk) & 3 of scale dword (2 s + fk) >> 2 = s >> 1, moved to byte 0
-    auto load_frags = [&](Frags& f, const unsigned char* stage, int s) {
-        const int sh = 16 * (s & 1) + 8 * fk;
+    // (2 s + fk) & 3 of scale dword (2 s + fk) >> 2 = s >> 1.  The dword is read once per pair of sub-steps
+    // and shifted by 8 fk bits, which puts the scale of the even sub-step in byte 0 and of the odd one in
+    // byte 2; the matrix instruction picks the byte (its scale operand select), so the odd sub-step takes
+    // the register of the even one (`even`) and reads nothing.
+    auto load_frags = [&](Frags& f, const unsigned char* stage, int s, const Frags& even) {
 #pragma unroll
         for (int i = 0; i < FM; ++i) {
             f.a[i] = *reinterpret_cast<const u32x4*>(stage + (aoff[i] ^ (s << 5)));
-            f.sa[i] = *reinterpret_cast<const uint32_t*>(stage + asoff[i] + (s >> 1) * ROWS * 4) >> sh;
+            if (s & 1) f.sa[i] = even.sa[i];
+            else f.sa[i] = *reinterpret_cast<const uint32_t*>(stage + asoff[i] + (s >> 1) * ROWS * 4) >> (8 * fk);
         }
 #pragma unroll
         for (int j = 0; j < FN; ++j) {
             f.b[j] = *reinterpret_cast<const u32x4*>(stage + (boff[j] ^ (s << 5)));
-            f.sb[j] = *reinterpret_cast<const uint32_t*>(stage + bsoff[j] + (s >> 1) * ROWS * 4) >> sh;
+            if (s & 1) f.sb[j] = even.sb[j];
+            else f.sb[j] = *reinterpret_cast<const uint32_t*>(stage + bsoff[j] + (s >> 1) * ROWS * 4) >> (8 * fk);
         }
     };
-    auto mfma_one = [&](const Frags& f, auto mc) {            // instruction m of the FM x FN of a sub-step
-        constexpr int i = decltype(mc)::value / FN, j = decltype(mc)::value % FN;
+    // formats 4 = FP4 E2M1 for both operands; odd: the sub-step's scales sit in byte 2 of the scale registers
+    auto mfma_ij = [&](const Frags& f, int i, int j, bool odd) {
         const i32x8 xa = {(int)f.a[i][0], (int)f.a[i][1], (int)f.a[i][2], (int)f.a[i][3], 0, 0, 0, 0};
         const i32x8 wb = {(int)f.b[j][0], (int)f.b[j][1], (int)f.b[j][2], (int)f.b[j][3], 0, 0, 0, 0};
-        acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wb, xa, acc[i][j], 4, 4, 0, (int)f.sb[j], 0,
-                                                                    (int)f.sa[i]);
+        if (odd)
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wb, xa, acc[i][j], 4, 4, 2, (int)f.sb[j], 2,
+                                                                        (int)f.sa[i]);
+        else
+            acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wb, xa, acc[i][j], 4, 4, 0, (int)f.sb[j], 0,
+                                                                        (int)f.sa[i]);
     };
-    auto mfma_all = [&](const Frags& f) {
+    auto mfma_one = [&](const Frags& f, auto mc, bool odd) {  // instruction m of the FM x FN of a sub-step
+        mfma_ij(f, decltype(mc)::value / FN, decltype(mc)::value % FN, odd);
+    };
+    auto mfma_all = [&](const Frags& f, bool odd) {
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            const i32x8 xa = {(int)f.a[i][0], (int)f.a[i][1], (int)f.a[i][2], (int)f.a[i][3], 0, 0, 0, 0};
+        for (int i = 0; i < FM; ++i)
 #pragma unroll
-            for (int j = 0; j < FN; ++j) {
-                const i32x8 wb = {(int)f.b[j][0], (int)f.b[j][1], (int)f.b[j][2], (int)f.b[j][3], 0, 0, 0, 0};
-                // formats 4 = FP4 E2M1 for both operands; scale byte 0 of each lane's scale register
-                acc[i][j] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(wb, xa, acc[i][j], 4, 4, 0, (int)f.sb[j], 0,
-                                                                            (int)f.sa[i]);
-            }
-        }
+            for (int j = 0; j < FN; ++j) mfma_ij(f, i, j, odd);
     };
 
     // Pipeline over sub-steps g = kt NSUB + s: read the fragments of g + 1 while the matrix cores work on g.
@@ -179,7 +183,7 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
     wait_vm<(NSTAGE - 1) * (CH + SCH)>();
     lds_barrier();
     Frags raw[2];
-    load_frags(raw[0], smem, 0);
+    load_frags(raw[0], smem, 0, raw[0]);
     int cur = 0;
     for (int kt = 0; kt + 1 < KT; ++kt) {
         const int nxt = (cur == NSTAGE - 1) ? 0 : cur + 1;
@@ -190,7 +194,7 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
             if (s == NSUB - 1) {
                 wait_vm<(NSTAGE - 2) * (CH + SCH)>();
                 lds_barrier();
-                load_frags(raw[(s + 1) & 1], snxt, 0);
+                load_frags(raw[(s + 1) & 1], snxt, 0, raw[s & 1]);
                 // refill the stage just left with K step kt + NSTAGE: the DMA instructions go between the
                 // matrix instructions, which keep the pipe busy while the wave is held up issuing them
                 const int ktn = min(kt + NSTAGE, KT - 1);
@@ -199,7 +203,7 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
                 static_for<NP>([&](auto pc) {
                     constexpr int c = decltype(pc)::value;
                     static_for<NM>([&](auto mc) {
-                        if constexpr (decltype(mc)::value * NP / NM == c) mfma_one(raw[s & 1], mc);
+                        if constexpr (decltype(mc)::value * NP / NM == c) mfma_one(raw[s & 1], mc, (s & 1) != 0);
                     });
                     __builtin_amdgcn_sched_barrier(0);
                     static_for<NSLOT>([&](auto qc) {
@@ -208,8 +212,8 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
                     __builtin_amdgcn_sched_barrier(0);
                 });
             } else {
-                load_frags(raw[(s + 1) & 1], scur, s + 1);
-                mfma_all(raw[s & 1]);
+                load_frags(raw[(s + 1) & 1], scur, s + 1, raw[s & 1]);
+                mfma_all(raw[s & 1], (s & 1) != 0);
             }
         }
         cur = nxt;
@@ -218,8 +222,8 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
         const unsigned char* scur = smem + cur * STAGE;
 #pragma unroll
         for (int s = 0; s < NSUB; ++s) {
-            if (s + 1 < NSUB) load_frags(raw[(s + 1) & 1], scur, s + 1);
-            mfma_all(raw[s & 1]);
+            if (s + 1 < NSUB) load_frags(raw[(s + 1) & 1], scur, s + 1, raw[s & 1]);
+            mfma_all(raw[s & 1], (s & 1) != 0);
         }
     }
     wait_vm<0>();
