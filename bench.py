@@ -275,10 +275,11 @@ def main() -> int:
                 continue
             wl2, b2 = prepare(name)
             s2 = wl2.spec
-            for _ in range(5):
-                pme.expanded_linear(b2["x"], s2.d_e, b2["qw"], b2["sw"], b2["y"], b2["ws"])
+            layer2 = lambda: pme.expanded_linear(b2["x"], s2.d_e, b2["qw"], b2["sw"], b2["y"], b2["ws"])
+            for _ in range(20):
+                layer2()
             it = 50
-            t_all = _event_ms(lambda: pme.expanded_linear(b2["x"], s2.d_e, b2["qw"], b2["sw"], b2["y"], b2["ws"]), it)
+            t_all = _graph_ms(layer2, it) or _event_ms(layer2, it, 5)
             tr, tg = stage_times(s2, b2, it)
             others[name] = {"layer_us": t_all * 1e3, "layer_tops": gemm_ops(s2) / (t_all * 1e-3) / 1e12,
                             "rotate_us": tr * 1e3, "rotate_gbs": algorithmic_bytes_rotate_quant(s2) / (tr * 1e-3) / 1e9,
