@@ -21,6 +21,7 @@ struct RotateArgs {
     uint8_t* ex;         // MXFP4: E8M0 scale bytes out [T, d_e / 32] (then qx holds E2M1 codes, sx is unused)
     float* xhat;         // fp32 rotated activations out (debug) or null
     hipStream_t stream;
+    int fold = 0;        // set by the MFMA launcher: butterfly stages folded into the base block (then b, k describe the folded shape)
 };
 
 struct MxGemmArgs {

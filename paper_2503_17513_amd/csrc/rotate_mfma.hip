@@ -151,9 +151,12 @@ __device__ __forceinline__ uint32_t split_hi(float f, float& rem) {
 constexpr int kMaxTiles = 10, kMaxKs = 5, kSlots = 8;
 __device__ __align__(256) u32x4 g_ptable[kSlots][kMaxTiles * kMaxKs][64];
 
-__global__ void __launch_bounds__(64) k_fill_ptable(int slot, int b, int rows) {
+// Fragments of the base block B = P_b (x) S_{2^fold} of order b 2^fold (fold = 0: the Paley block itself).
+// Folding the first `fold` butterfly stages into the block leaves H = P_b (x) S_{2^k} unchanged, since
+// S_{2^k} = S_{2^fold} (x) S_{2^(k - fold)}: entry ((a, u), (a', u')) = P[a][a'] (-1)^popcount(u & u').
+__global__ void __launch_bounds__(64) k_fill_ptable(int slot, int b, int fold, int rows) {
     __shared__ signed char chi[256];
-    const int lane = threadIdx.x, q = b - 1;
+    const int lane = threadIdx.x, q = b - 1, border = b << fold, umask = (1 << fold) - 1;
     if (b > 1) {
         for (int i = lane; i < q; i += 64) chi[i] = (i == 0) ? 0 : -1;
         __syncthreads();
@@ -170,8 +173,9 @@ __global__ void __launch_bounds__(64) k_fill_ptable(int slot, int b, int rows) {
         for (int h = 0; h < 2; ++h) {
             const int a = 32 * ks + 8 * g + 2 * p + h;
             uint32_t bits = 0;
-            if (a < rows && a < b && ap < b) {
-                const int sgn = (b > 1) ? paley_entry(chi, q, a, ap) : 1;
+            if (a < rows && a < border && ap < border) {
+                int sgn = (b > 1) ? paley_entry(chi, q, a >> fold, ap >> fold) : 1;
+                if (__popc((unsigned)(a & ap & umask)) & 1) sgn = -sgn;
                 bits = sgn > 0 ? 0x3F80u : 0xBF80u;
             }
             word |= bits << (16 * h);
@@ -181,25 +185,27 @@ __global__ void __launch_bounds__(64) k_fill_ptable(int slot, int b, int rows) {
     g_ptable[slot][blockIdx.x][lane] = pk;
 }
 
-struct TableKey { int device, b, rows; };
+struct TableKey { int device, b, fold, rows; };
 std::mutex g_table_mutex;
 TableKey g_table_keys[kSlots];
 int g_table_used = 0, g_table_next = 0;
 
-// Returns the slot holding the table for (b, rows) on the current device, building it on a miss.
+// Returns the slot holding the table for (b, fold, rows) on the current device, building it on a miss.
 // A miss launches the fill kernel on `stream` and waits for it once, so that callers on other
 // streams never see a half-written table.  With more than kSlots live shapes per process the
 // oldest slot is reused; calls still in flight on that shape would then race with the refill.
-int table_slot(int b, int rows, hipStream_t stream, pme_status* st) {
+int table_slot(int b, int fold, int rows, hipStream_t stream, pme_status* st) {
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) { *st = PME_ERR_HIP; return -1; }
     std::lock_guard<std::mutex> lock(g_table_mutex);
     for (int i = 0; i < g_table_used; ++i)
-        if (g_table_keys[i].device == dev && g_table_keys[i].b == b && g_table_keys[i].rows == rows) return i;
+        if (g_table_keys[i].device == dev && g_table_keys[i].b == b && g_table_keys[i].fold == fold &&
+            g_table_keys[i].rows == rows)
+            return i;
     const int slot = g_table_next;
-    hipLaunchKernelGGL(k_fill_ptable, dim3(kMaxTiles * kMaxKs), dim3(64), 0, stream, slot, b, rows);
+    hipLaunchKernelGGL(k_fill_ptable, dim3(kMaxTiles * kMaxKs), dim3(64), 0, stream, slot, b, fold, rows);
     if (hipGetLastError() != hipSuccess || hipStreamSynchronize(stream) != hipSuccess) { *st = PME_ERR_HIP; return -1; }
-    g_table_keys[slot] = TableKey{dev, b, rows};
+    g_table_keys[slot] = TableKey{dev, b, fold, rows};
     g_table_next = (g_table_next + 1) % kSlots;
     if (g_table_used < kSlots) ++g_table_used;
     return slot;
@@ -604,7 +610,7 @@ pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     if (lds > kMaxDynLds || nwaves > max_waves<KLOG2, TPW>()) return PME_ERR_UNSUPPORTED_PATH;
     const int rows = (int)((a.d + L::NC - 1) >> KLOG2);
     pme_status st = PME_OK;
-    const int slot = table_slot(a.b, rows, a.stream, &st);
+    const int slot = table_slot(a.b >> a.fold, a.fold, rows, a.stream, &st);
     if (slot < 0) return st;
     auto kern = k_rotate_mfma<KLOG2, TPW, F32IN, OUT>;
     // the same kernel runs with different LDS sizes (they follow the shape): allow the largest one accepted above
@@ -632,7 +638,7 @@ pme_status launch_multi_out(const RotateArgs& a, int ks) {
     if (lds > kMaxDynLds) return PME_ERR_UNSUPPORTED_PATH;
     const int rows = (int)((a.d + L::NC - 1) >> KLOG2);
     pme_status st = PME_OK;
-    const int slot = table_slot(a.b, rows, a.stream, &st);
+    const int slot = table_slot(a.b >> a.fold, a.fold, rows, a.stream, &st);
     if (slot < 0) return st;
     auto kern = k_rotate_mfma<KLOG2, TPW, false, OUT, true>;
     static std::atomic<uint32_t> done;
@@ -669,10 +675,20 @@ int g_multi_override = -1;     // experiments: 0 / 1 force the multi-token varia
 
 void set_rotate_tpw_override(int tpw) { g_tpw_override = tpw; }
 
-pme_status launch_rotate_mfma(const RotateArgs& a) {
-    // Shapes covered: 32 <= 2^k <= 512.  bf16 input is copied to LDS in 16-byte pieces, so d, the row
-    // pitch and the base address must be multiples of 8 elements; code rows must be 16-byte aligned.
-    if (a.k < 5 || a.k > 9) return PME_ERR_UNSUPPORTED_PATH;
+pme_status launch_rotate_mfma(const RotateArgs& in) {
+    // Shapes covered: 2^k >= 32; in-register butterflies span at most 512 columns, so for larger 2^k the
+    // first k - 9 stages are folded into the base block (order b 2^(k-9), at most 160), which the matrix
+    // cores apply: the kernel sees the same transform as a block of that order times 512 columns.
+    // bf16 input is copied to LDS in 16-byte pieces, so d, the row pitch and the base address must be
+    // multiples of 8 elements; code rows must be 16-byte aligned.
+    RotateArgs a = in;
+    if (a.k > 9) {
+        a.fold = a.k - 9;
+        if (a.fold > 8 || ((int64_t)a.b << a.fold) > 16 * kMaxTiles) return PME_ERR_UNSUPPORTED_PATH;
+        a.b <<= a.fold;
+        a.k = 9;
+    }
+    if (a.k < 5) return PME_ERR_UNSUPPORTED_PATH;
     const bool f32 = a.xt == PME_F32;
     if (!f32 && ((a.d & 7) || (a.ldx & 7) || (reinterpret_cast<uintptr_t>(a.x) & 15))) return PME_ERR_UNSUPPORTED_PATH;
     if (a.qx && (reinterpret_cast<uintptr_t>(a.qx) & 15)) return PME_ERR_UNSUPPORTED_PATH;

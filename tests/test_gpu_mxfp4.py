@@ -63,6 +63,7 @@ QUANT_CASES = [
     ("f32_b68_k5", 6, 2048, 2176, "f32", (GENERIC, MFMA)),
     ("many_tokens_k7", 530, 8192, 8704, "bf16", (MFMA,)),
     ("b68_k5_token_per_wave", 1029, 2048, 2176, "bf16", (MFMA,)),
+    ("b12_k10_folded", 5, 8192, 12288, "bf16", (GENERIC, MFMA)),
 ]
 
 

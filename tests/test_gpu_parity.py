@@ -39,14 +39,20 @@ ROTATE_CASES = [
     ("f32_b132_k6", 3, 8192, 8448, "f32", (GENERIC, MFMA)),
     ("pow2_ratio_one", 5, 256, 256, "bf16", (GENERIC, MFMA)),
     ("pow2_padded", 5, 200, 256, "f32", (GENERIC, MFMA)),
-    ("pow2_k12", 3, 4096, 4096, "bf16", (GENERIC,)),
+    # 2^k > 512: the matrix-core kernel folds the first k - 9 butterfly stages into the base block
+    ("pow2_k12", 3, 4096, 4096, "bf16", (GENERIC, MFMA)),
+    ("pow2_k10_ragged_d", 5, 1000, 1024, "bf16", (GENERIC, MFMA)),
+    ("pow2_k13_f32", 3, 8192, 8192, "f32", (GENERIC, MFMA)),
+    ("pow2_k15", 2, 30000, 32768, "bf16", (GENERIC, MFMA)),
+    ("b12_k10_many_tokens", 300, 8192, 12288, "bf16", (MFMA,)),
+    ("b20_k11", 3, 36000, 40960, "bf16", (MFMA,)),          # 160 KB of fp32: beyond the generic kernel's LDS buffer
     ("b12_k6", 4, 696, 768, "bf16", (GENERIC, MFMA)),
     ("b20_k5", 4, 600, 640, "bf16", (GENERIC, MFMA)),
     ("b72_k5", 4, 2104, 2304, "bf16", (GENERIC, MFMA)),
     ("b140_k6", 3, 8192, 8960, "bf16", (GENERIC, MFMA)),
     ("b152_k6", 3, 8192, 9728, "bf16", (GENERIC, MFMA)),
     ("b20_k9", 3, 8192, 10240, "bf16", (GENERIC, MFMA)),
-    ("b12_k10", 2, 8192, 12288, "bf16", (GENERIC,)),
+    ("b12_k10", 2, 8192, 12288, "bf16", (GENERIC, MFMA)),
     ("single_token", 1, 2048, 2176, "bf16", (GENERIC, MFMA)),
     # 1024 tokens or more at 2^k = 32: workgroups whose waves each rotate tokens of their own (token counts
     # that do not divide by the waves of a workgroup, one- and five-tile blocks, ragged d)
@@ -100,7 +106,8 @@ def test_rotate_strided_rows(path):
 
 ASYM_CASES = [("tiny", 16, 64, 80, "f32", (GENERIC,)), ("b68_k5", 9, 2048, 2176, "bf16", (GENERIC, MFMA)),
               ("b60_k8", 4, 14336, 15360, "bf16", (GENERIC, MFMA)),
-              ("b68_k5_token_per_wave", 1026, 2048, 2176, "bf16", (MFMA,))]
+              ("b68_k5_token_per_wave", 1026, 2048, 2176, "bf16", (MFMA,)),
+              ("b12_k10_folded", 5, 8192, 12288, "bf16", (GENERIC, MFMA))]
 
 
 @pytest.mark.parametrize("name,T,d,d_e,in_dtype,paths", ASYM_CASES, ids=[c[0] for c in ASYM_CASES])
