@@ -48,7 +48,9 @@ typedef enum {
     PME_ERR_WORKSPACE = 5,          /* workspace too small */
     PME_ERR_DTYPE = 6,              /* unknown pme_dtype */
     PME_ERR_HIP = 7,                /* the HIP runtime refused a launch */
-    PME_ERR_UNSUPPORTED_PATH = 8    /* the kernel path forced with pme_set_path cannot run this shape */
+    PME_ERR_UNSUPPORTED_PATH = 8    /* no kernel path (or not the one forced with pme_set_path) runs this shape:
+                                       e.g. a token of more than about 40000 expanded features whose block the
+                                       matrix-core kernel does not take */
 } pme_status;
 
 typedef enum { PME_F32 = 0, PME_BF16 = 1 } pme_dtype;

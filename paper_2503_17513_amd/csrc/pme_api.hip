@@ -312,7 +312,7 @@ const char* pme_status_string(pme_status s) {
         case PME_ERR_WORKSPACE: return "workspace too small";
         case PME_ERR_DTYPE: return "unknown dtype";
         case PME_ERR_HIP: return "HIP launch failed";
-        case PME_ERR_UNSUPPORTED_PATH: return "forced kernel path does not cover this shape";
+        case PME_ERR_UNSUPPORTED_PATH: return "no kernel path (or not the forced one) covers this shape";
     }
     return "unknown status";
 }
