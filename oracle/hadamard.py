@@ -15,7 +15,7 @@ import numpy as np
 
 # Base orders b = q + 1 with q prime, q = 3 (mod 4), keyed by the odd part of b.
 # b = 1 is the pure power-of-two case (expansion ratio 1.0 in Section 4).
-SUPPORTED_BASE = (1, 12, 20, 60, 68, 72, 132, 140, 152)
+SUPPORTED_BASE = (1, 12, 20, 60, 68, 72, 132, 140, 152, 312)
 
 
 def sylvester(k: int) -> np.ndarray:

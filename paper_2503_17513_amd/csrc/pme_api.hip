@@ -11,7 +11,7 @@ std::atomic<int> g_path{PME_PATH_AUTO};
 
 // Base orders b = q + 1, q prime and congruent to 3 mod 4, with pairwise distinct odd parts,
 // so that d_e = b * 2^k has at most one solution.  b = 1: plain power of two.
-const int kBaseOrders[] = {1, 12, 20, 60, 68, 72, 132, 140, 152};
+const int kBaseOrders[] = {1, 12, 20, 60, 68, 72, 132, 140, 152, 312};
 
 bool factor_order(int64_t d_e, int* b, int* k) {
     if (d_e <= 0) return false;
@@ -261,7 +261,7 @@ pme_status pme_base_block(int64_t b, int8_t* out) {
     if (b == 1) { out[0] = 1; return PME_OK; }
     const int q = (int)b - 1;
     // quadratic character of GF(q) by marking the squares
-    int8_t chi[256];
+    int8_t chi[512];
     for (int i = 0; i < q; ++i) chi[i] = -1;
     chi[0] = 0;
     for (int i = 1; i < q; ++i) chi[(i * i) % q] = 1;

@@ -155,7 +155,7 @@ k_rotate_generic(const InT* __restrict__ x, int64_t ldx, int d, int d_e, int b, 
 }  // namespace
 
 pme_status launch_rotate_generic(const RotateArgs& a) {
-    const size_t lds = (size_t)a.d_e * 4 + 8 * 4 + 256;
+    const size_t lds = (size_t)a.d_e * 4 + 8 * 4 + 512;      // token as fp32, reduction scratch, quadratic characters (q <= 311)
     if (lds > 160 * 1024) return PME_ERR_UNSUPPORTED_PATH;
     const double gamma = 1.0 / sqrt((double)a.d_e);
     hipError_t e = hipSuccess;

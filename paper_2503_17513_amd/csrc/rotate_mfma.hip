@@ -148,14 +148,14 @@ __device__ __forceinline__ uint32_t split_hi(float f, float& rem) {
 // Entry (tile, ks), lane (a' = 16 tile + lane % 16, g = lane / 16) holds P[32 ks + 8 g + e][a'],
 // e = 0..7 (+-1 in bf16; 0 outside the block or beyond the rows that hold real inputs).
 // ---------------------------------------------------------------------------------------------
-constexpr int kMaxTiles = 10, kMaxKs = 5, kSlots = 8;
+constexpr int kMaxTiles = 20, kMaxKs = 7, kSlots = 8;     // blocks up to order 320, up to 224 real base rows
 __device__ __align__(256) u32x4 g_ptable[kSlots][kMaxTiles * kMaxKs][64];
 
 // Fragments of the base block B = P_b (x) S_{2^fold} of order b 2^fold (fold = 0: the Paley block itself).
 // Folding the first `fold` butterfly stages into the block leaves H = P_b (x) S_{2^k} unchanged, since
 // S_{2^k} = S_{2^fold} (x) S_{2^(k - fold)}: entry ((a, u), (a', u')) = P[a][a'] (-1)^popcount(u & u').
 __global__ void __launch_bounds__(64) k_fill_ptable(int slot, int b, int fold, int rows) {
-    __shared__ signed char chi[256];
+    __shared__ signed char chi[512];
     const int lane = threadIdx.x, q = b - 1, border = b << fold, umask = (1 << fold) - 1;
     if (b > 1) {
         for (int i = lane; i < q; i += 64) chi[i] = (i == 0) ? 0 : -1;
@@ -238,7 +238,9 @@ __device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t
 // refilled for the next token as soon as the matrix-core phase of the current one has consumed it,
 // so the HBM read of token i + 1 runs under the FWHT / quantize / store phase of token i.
 // Most waves a workgroup of this instantiation is launched with (bounds the registers per lane).
-template <int KLOG2, int TPW> constexpr int max_waves() { return (TPW == 1 && KLOG2 <= 8) ? kMaxWaves : kMaxWaves / 2; }
+template <int KLOG2, int TPW> constexpr int max_waves() {
+    return ((TPW == 1 && KLOG2 <= 8) || (KLOG2 == 6 && TPW == 2)) ? kMaxWaves : kMaxWaves / 2;
+}
 
 enum { OUT_SYM = 0, OUT_ASYM = 1, OUT_XHAT = 2, OUT_MXFP4 = 3 };   // int4 symmetric / asymmetric codes, fp32 values, MXFP4
 
@@ -246,7 +248,9 @@ enum { OUT_SYM = 0, OUT_ASYM = 1, OUT_XHAT = 2, OUT_MXFP4 = 3 };   // int4 symme
 // rotates tokens of its own, in a token buffer of its own; only the B fragments are shared.  Compared
 // with one-wave workgroups this loads the fragments once per several tokens and hands the dispatcher
 // fewer workgroups, which is what counts at small 2^k, where a token is only a few KB.
-template <int KLOG2, int TPW, bool F32IN, int OUT, bool MULTI = false>
+// BGLOBAL: the P fragments are not staged in LDS but read from the table in device memory (L2) for every
+// token: for blocks whose fragments do not fit beside the token buffer (order 312: 140 KB of fragments).
+template <int KLOG2, int TPW, bool F32IN, int OUT, bool MULTI = false, bool BGLOBAL = false>
 __global__ void __launch_bounds__((64 * max_waves<KLOG2, TPW>()))
 k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, int b, int ks_count, int slot,
               double gamma, uint8_t* __restrict__ qx, float* __restrict__ sx, int32_t* __restrict__ zx,
@@ -345,7 +349,9 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
         if (t < T) load_token_dma(t);       // in flight while the B fragments are fetched
     }
     // ---- once per workgroup: B fragments of P into LDS
-    if constexpr (MULTI) {
+    if constexpr (BGLOBAL) {
+        // nothing to stage
+    } else if constexpr (MULTI) {
         for (int f = wave_hw; f < TPW * ks_count; f += nwaves_hw) {       // fragment f = ti ks_count + ks
             const int tile = min(f / ks_count, kMaxTiles - 1);
             *reinterpret_cast<u32x4*>(bsm + ((size_t)f * 64 + lane) * 16) = g_ptable[slot][tile * kMaxKs + f % ks_count][lane];
@@ -386,7 +392,10 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
             bf16x8 bfrag[TPW];
 #pragma unroll
             for (int ti = 0; ti < TPW; ++ti)
-                bfrag[ti] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(bsm + ((size_t)(ti * ks_count + ks) * 64 + lane) * 16));
+                if constexpr (BGLOBAL)
+                    bfrag[ti] = __builtin_bit_cast(bf16x8, g_ptable[slot][min(wave * TPW + ti, kMaxTiles - 1) * kMaxKs + ks][lane]);
+                else
+                    bfrag[ti] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(bsm + ((size_t)(ti * ks_count + ks) * 64 + lane) * 16));
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 if constexpr (!F32IN) {
@@ -600,11 +609,11 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
     wait_all_vm();
 }
 
-template <int KLOG2, int TPW, bool F32IN, int OUT>
+template <int KLOG2, int TPW, bool F32IN, int OUT, bool BGLOBAL = false>
 pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     using L = Layout<KLOG2>;
     constexpr int NS = F32IN ? 3 : 1;
-    const size_t lds = (size_t)NS * ks * L::MT * 1024 + (size_t)nwaves * TPW * ks * 1024;
+    const size_t lds = (size_t)NS * ks * L::MT * 1024 + (BGLOBAL ? 0 : (size_t)nwaves * TPW * ks * 1024);
     // 160 KB per workgroup, less the kernel's static LDS rounded up to the dynamic part's 1 KB alignment
     constexpr size_t kMaxDynLds = 160 * 1024 - 1024;
     if (lds > kMaxDynLds || nwaves > max_waves<KLOG2, TPW>()) return PME_ERR_UNSUPPORTED_PATH;
@@ -612,7 +621,7 @@ pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     pme_status st = PME_OK;
     const int slot = table_slot(a.b >> a.fold, a.fold, rows, a.stream, &st);
     if (slot < 0) return st;
-    auto kern = k_rotate_mfma<KLOG2, TPW, F32IN, OUT>;
+    auto kern = k_rotate_mfma<KLOG2, TPW, F32IN, OUT, false, BGLOBAL>;
     // the same kernel runs with different LDS sizes (they follow the shape): allow the largest one accepted above
     static std::atomic<uint32_t> done;
     if (lds > 48 * 1024 && allow_dynamic_lds(kern, (int)kMaxDynLds, done) != PME_OK) return PME_ERR_HIP;
@@ -660,12 +669,12 @@ pme_status launch_multi(const RotateArgs& a, int ks) {
     return launch_multi_out<KLOG2, TPW, OUT_SYM>(a, ks);
 }
 
-template <int KLOG2, int TPW, bool F32IN>
+template <int KLOG2, int TPW, bool F32IN, bool BGLOBAL = false>
 pme_status launch_one(const RotateArgs& a, int ks, int nwaves) {
-    if (a.xhat) return launch_out<KLOG2, TPW, F32IN, OUT_XHAT>(a, ks, nwaves);
-    if (a.ex) return launch_out<KLOG2, TPW, F32IN, OUT_MXFP4>(a, ks, nwaves);
-    if (a.zx) return launch_out<KLOG2, TPW, F32IN, OUT_ASYM>(a, ks, nwaves);
-    return launch_out<KLOG2, TPW, F32IN, OUT_SYM>(a, ks, nwaves);
+    if (a.xhat) return launch_out<KLOG2, TPW, F32IN, OUT_XHAT, BGLOBAL>(a, ks, nwaves);
+    if (a.ex) return launch_out<KLOG2, TPW, F32IN, OUT_MXFP4, BGLOBAL>(a, ks, nwaves);
+    if (a.zx) return launch_out<KLOG2, TPW, F32IN, OUT_ASYM, BGLOBAL>(a, ks, nwaves);
+    return launch_out<KLOG2, TPW, F32IN, OUT_SYM, BGLOBAL>(a, ks, nwaves);
 }
 
 int g_tpw_override = 0;
@@ -709,6 +718,9 @@ pme_status launch_rotate_mfma(const RotateArgs& in) {
     // few tokens: spread a token over as many waves as it has tiles
     if (a.T < 512 && a.k <= 8) tpw = 1;
     if (g_tpw_override > 0) tpw = g_tpw_override;
+    // The order-312 block at 2^k = 64 (19968 = 312 x 64): 20 column tiles on 10 waves; its fragments
+    // (nt ks KB) do not fit in LDS beside the token and are read from the table in device memory.
+    if (!f32 && a.k == 6 && nt > kMaxWaves && g_tpw_override == 0) return launch_one<6, 2, false, true>(a, ks, (nt + 1) / 2);
     const int nwaves = (nt + tpw - 1) / tpw;
     if (nwaves > kMaxWaves) return PME_ERR_UNSUPPORTED_PATH;
     // 2^k = 32 with a block of at most 80: the token is one wave's work and only a few KB

@@ -64,6 +64,7 @@ QUANT_CASES = [
     ("many_tokens_k7", 530, 8192, 8704, "bf16", (MFMA,)),
     ("b68_k5_token_per_wave", 1029, 2048, 2176, "bf16", (MFMA,)),
     ("b12_k10_folded", 5, 8192, 12288, "bf16", (GENERIC, MFMA)),
+    ("b312_k6", 5, 14336, 19968, "bf16", (GENERIC, MFMA)),
 ]
 
 

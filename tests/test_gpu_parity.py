@@ -51,6 +51,9 @@ ROTATE_CASES = [
     ("b72_k5", 4, 2104, 2304, "bf16", (GENERIC, MFMA)),
     ("b140_k6", 3, 8192, 8960, "bf16", (GENERIC, MFMA)),
     ("b152_k6", 3, 8192, 9728, "bf16", (GENERIC, MFMA)),
+    # 20 column tiles on 10 waves, P fragments read from device memory
+    ("b312_k6", 3, 14336, 19968, "bf16", (GENERIC, MFMA)),
+    ("b312_k6_many_tokens_ragged_d", 290, 14000, 19968, "bf16", (MFMA,)),
     ("b20_k9", 3, 8192, 10240, "bf16", (GENERIC, MFMA)),
     ("b12_k10", 2, 8192, 12288, "bf16", (GENERIC, MFMA)),
     ("single_token", 1, 2048, 2176, "bf16", (GENERIC, MFMA)),
@@ -107,7 +110,8 @@ def test_rotate_strided_rows(path):
 ASYM_CASES = [("tiny", 16, 64, 80, "f32", (GENERIC,)), ("b68_k5", 9, 2048, 2176, "bf16", (GENERIC, MFMA)),
               ("b60_k8", 4, 14336, 15360, "bf16", (GENERIC, MFMA)),
               ("b68_k5_token_per_wave", 1026, 2048, 2176, "bf16", (MFMA,)),
-              ("b12_k10_folded", 5, 8192, 12288, "bf16", (GENERIC, MFMA))]
+              ("b12_k10_folded", 5, 8192, 12288, "bf16", (GENERIC, MFMA)),
+              ("b312_k6", 5, 14336, 19968, "bf16", (GENERIC, MFMA))]
 
 
 @pytest.mark.parametrize("name,T,d,d_e,in_dtype,paths", ASYM_CASES, ids=[c[0] for c in ASYM_CASES])

@@ -15,7 +15,7 @@ from workloads import make_workload
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 ORDERS = (80, 2176, 8704, 8448, 15360)
-BASES = (12, 20, 60, 68, 72, 132, 140, 152)
+BASES = (12, 20, 60, 68, 72, 132, 140, 152, 312)
 
 
 def _signs(line):
@@ -99,7 +99,8 @@ def test_factor_order_gives_the_workload_factorisations():
     assert oracle.factor_order(10240) == (20, 9)
     assert oracle.factor_order(12288) == (12, 10)
     assert oracle.factor_order(18432) == (72, 8)
-    for bad in (7, 100, 19968, 22016):
+    assert oracle.factor_order(19968) == (312, 6)
+    for bad in (7, 100, 22016):
         with pytest.raises(ValueError):
             oracle.factor_order(bad)
 
