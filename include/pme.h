@@ -10,8 +10,9 @@
  * T, d, d_e, N here.
  *
  * The Hadamard matrix of order d_e = b * 2^k is H = P_b (x) S_{2^k}: a Paley type-I
- * block of order b (b - 1 prime and congruent to 3 mod 4; b = 1 for a pure power of
- * two) Kronecker the natural-order Sylvester matrix; matrix index i = a * 2^k + c.
+ * block of order b (b - 1 a prime congruent to 3 mod 4, or 7^3; b = 1 for a pure power
+ * of two; supported: 1, 12, 20, 60, 68, 72, 132, 140, 152, 312, 344) Kronecker the
+ * natural-order Sylvester matrix; matrix index i = a * 2^k + c.
  * The paper leaves the construction open ("a deterministic Hadamard matrix",
  * Section 4); pme_base_block exports the block actually used.
  *

@@ -13,9 +13,9 @@ from __future__ import annotations
 
 import numpy as np
 
-# Base orders b = q + 1 with q prime, q = 3 (mod 4), keyed by the odd part of b.
-# b = 1 is the pure power-of-two case (expansion ratio 1.0 in Section 4).
-SUPPORTED_BASE = (1, 12, 20, 60, 68, 72, 132, 140, 152, 312)
+# Base orders b = q + 1 with q a prime (or, for 344, the prime power 7^3), q = 3 (mod 4), keyed by the
+# odd part of b.  b = 1 is the pure power-of-two case (expansion ratio 1.0 in Section 4).
+SUPPORTED_BASE = (1, 12, 20, 60, 68, 72, 132, 140, 152, 312, 344)
 
 
 def sylvester(k: int) -> np.ndarray:
@@ -34,21 +34,69 @@ def legendre_symbol(a: int, q: int) -> int:
     return 1 if pow(a, (q - 1) // 2, q) == 1 else -1
 
 
-def paley_block(b: int) -> np.ndarray:
-    """Paley type-I Hadamard matrix of order b = q + 1, q prime, q = 3 (mod 4).
+# GF(7^3) = GF(7)[t] / (t^3 + t + 1); the cubic has no root in GF(7), hence is irreducible.  Element number
+# e = c0 + 7 c1 + 49 c2 stands for c0 + c1 t + c2 t^2.
+GF343_P, GF343_MODULUS = 7, (1, 1, 0, 1)          # coefficients of 1 + t + 0 t^2 + t^3
 
-    Jacobsthal matrix Q[i][j] = chi((i - j) mod q); skew matrix S = [[0, 1^T], [-1, Q]];
-    P_b = I + S.  b = 1 returns [[1]].  int64 entries +-1.
+
+def gf343_digits(e: int) -> tuple[int, int, int]:
+    return e % 7, (e // 7) % 7, e // 49
+
+
+def gf343_sub(e: int, f: int) -> int:
+    """Number of the field element e - f (coefficient-wise, mod 7)."""
+    a, b = gf343_digits(e), gf343_digits(f)
+    c = [(x - y) % 7 for x, y in zip(a, b)]
+    return c[0] + 7 * c[1] + 49 * c[2]
+
+
+def gf343_mul(e: int, f: int) -> int:
+    """Number of the field element e f: polynomial product, then t^3 = -t - 1 twice (degrees 4 and 3)."""
+    a, b = gf343_digits(e), gf343_digits(f)
+    prod = [0] * 5
+    for i in range(3):
+        for j in range(3):
+            prod[i + j] += a[i] * b[j]
+    for deg in (4, 3):                 # t^deg = t^(deg-3) t^3 = -(t^(deg-2) + t^(deg-3))
+        c = prod[deg]
+        prod[deg] = 0
+        prod[deg - 2] -= c
+        prod[deg - 3] -= c
+    c = [v % 7 for v in prod[:3]]
+    return c[0] + 7 * c[1] + 49 * c[2]
+
+
+def gf343_quadratic_character() -> np.ndarray:
+    """chi over GF(343) by element number: 0 at zero, +1 at the non-zero squares, -1 elsewhere."""
+    chi = -np.ones(343, dtype=np.int64)
+    chi[0] = 0
+    for e in range(1, 343):
+        chi[gf343_mul(e, e)] = 1
+    return chi
+
+
+def paley_block(b: int) -> np.ndarray:
+    """Paley type-I Hadamard matrix of order b = q + 1, q = 3 (mod 4) a prime or 7^3.
+
+    Jacobsthal matrix Q[i][j] = chi(x_i - x_j) over GF(q), the elements numbered 0 .. q-1 (a prime field:
+    the residues; GF(343): see above); skew matrix S = [[0, 1^T], [-1, Q]]; P_b = I + S.
+    b = 1 returns [[1]].  int64 entries +-1.
     """
     if b == 1:
         return np.ones((1, 1), dtype=np.int64)
     q = b - 1
-    if q % 4 != 3 or any(q % p == 0 for p in range(2, int(q ** 0.5) + 1)):
-        raise ValueError(f"order {b}: q = {q} is not a prime congruent to 3 mod 4")
     Q = np.empty((q, q), dtype=np.int64)
-    for i in range(q):
-        for j in range(q):
-            Q[i, j] = legendre_symbol(i - j, q)
+    if q == 343:
+        chi = gf343_quadratic_character()
+        for i in range(q):
+            for j in range(q):
+                Q[i, j] = chi[gf343_sub(i, j)]
+    else:
+        if q % 4 != 3 or any(q % p == 0 for p in range(2, int(q ** 0.5) + 1)):
+            raise ValueError(f"order {b}: q = {q} is not a prime congruent to 3 mod 4")
+        for i in range(q):
+            for j in range(q):
+                Q[i, j] = legendre_symbol(i - j, q)
     S = np.zeros((b, b), dtype=np.int64)
     S[0, 1:] = 1
     S[1:, 0] = -1

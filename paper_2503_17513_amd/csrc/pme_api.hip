@@ -11,7 +11,7 @@ std::atomic<int> g_path{PME_PATH_AUTO};
 
 // Base orders b = q + 1, q prime and congruent to 3 mod 4, with pairwise distinct odd parts,
 // so that d_e = b * 2^k has at most one solution.  b = 1: plain power of two.
-const int kBaseOrders[] = {1, 12, 20, 60, 68, 72, 132, 140, 152, 312};
+const int kBaseOrders[] = {1, 12, 20, 60, 68, 72, 132, 140, 152, 312, 344};
 
 bool factor_order(int64_t d_e, int* b, int* k) {
     if (d_e <= 0) return false;
@@ -264,14 +264,14 @@ pme_status pme_base_block(int64_t b, int8_t* out) {
     int8_t chi[512];
     for (int i = 0; i < q; ++i) chi[i] = -1;
     chi[0] = 0;
-    for (int i = 1; i < q; ++i) chi[(i * i) % q] = 1;
+    for (int i = 1; i < q; ++i) chi[pme::gf_square(q, i)] = 1;
     for (int a = 0; a < b; ++a)
         for (int ap = 0; ap < b; ++ap) {
             int v;
             if (a == 0) v = 1;
             else if (ap == 0) v = -1;
             else if (a == ap) v = 1;
-            else v = chi[((a - ap) % q + q) % q];
+            else v = chi[pme::gf_sub(q, a - 1, ap - 1)];
             out[a * b + ap] = (int8_t)v;
         }
     return PME_OK;

@@ -144,13 +144,44 @@ __device__ __forceinline__ uint32_t mx_pack8(float f0, float f1, float f2, float
 
 // Entry P[a][ap] of the Paley type-I block I + [[0, 1^T], [-1, Q]], Q[i][j] = chi((i - j) mod q),
 // given the table chi[0..q-1] of the quadratic character.  b = q + 1.
+// Field arithmetic behind the Paley blocks, by element number: GF(q) for the primes q = b - 1 in use (the
+// residues) and GF(343) = GF(7)[t] / (t^3 + t + 1), where c0 + 7 c1 + 49 c2 stands for c0 + c1 t + c2 t^2
+// (the cubic has no root in GF(7), hence is irreducible).
+__host__ __device__ inline int gf_sub(int q, int i, int j) {
+    if (q != 343) {
+        const int d = i - j;
+        return d < 0 ? d + q : d;
+    }
+    const int d0 = (i % 7 - j % 7 + 7) % 7, d1 = ((i / 7) % 7 - (j / 7) % 7 + 7) % 7, d2 = (i / 49 - j / 49 + 7) % 7;
+    return d0 + 7 * d1 + 49 * d2;
+}
+__host__ __device__ inline int gf_square(int q, int i) {
+    if (q != 343) return (int)(((long long)i * i) % q);
+    const int a0 = i % 7, a1 = (i / 7) % 7, a2 = i / 49;
+    // (a0 + a1 t + a2 t^2)^2, then t^4 = -t^2 - t and t^3 = -t - 1
+    int p0 = a0 * a0, p1 = 2 * a0 * a1, p2 = 2 * a0 * a2 + a1 * a1, p3 = 2 * a1 * a2, p4 = a2 * a2;
+    p2 -= p4; p1 -= p4;
+    p1 -= p3; p0 -= p3;
+    p0 = ((p0 % 7) + 7) % 7; p1 = ((p1 % 7) + 7) % 7; p2 = ((p2 % 7) + 7) % 7;
+    return p0 + 7 * p1 + 49 * p2;
+}
+// Quadratic character table of GF(q): chi[0] = 0, +1 at the non-zero squares, -1 elsewhere; threads
+// tid, tid + nthreads, ... of a workgroup fill it together (two passes with a barrier between them).
+#define PME_FILL_CHI(chi, q, tid, nthreads)                                          \
+    do {                                                                             \
+        for (int i_ = (tid); i_ < (q); i_ += (nthreads)) (chi)[i_] = (i_ == 0) ? 0 : -1; \
+        __syncthreads();                                                             \
+        for (int i_ = 1 + (tid); i_ < (q); i_ += (nthreads)) (chi)[gf_square((q), i_)] = 1; \
+        __syncthreads();                                                             \
+    } while (0)
+
+// Entry (a, a') of the Paley block P = I + [[0, 1^T], [-1, Q]], Q[i][j] = chi(x_i - x_j), block index a >= 1
+// standing for field element a - 1.
 __device__ __forceinline__ int paley_entry(const signed char* chi, int q, int a, int ap) {
     if (a == 0) return 1;
     if (ap == 0) return -1;
     if (a == ap) return 1;
-    int dlt = a - ap;
-    if (dlt < 0) dlt += q;
-    return chi[dlt];
+    return chi[gf_sub(q, a - 1, ap - 1)];
 }
 
 }  // namespace pme

@@ -148,7 +148,7 @@ __device__ __forceinline__ uint32_t split_hi(float f, float& rem) {
 // Entry (tile, ks), lane (a' = 16 tile + lane % 16, g = lane / 16) holds P[32 ks + 8 g + e][a'],
 // e = 0..7 (+-1 in bf16; 0 outside the block or beyond the rows that hold real inputs).
 // ---------------------------------------------------------------------------------------------
-constexpr int kMaxTiles = 20, kMaxKs = 7, kSlots = 8;     // blocks up to order 320, up to 224 real base rows
+constexpr int kMaxTiles = 22, kMaxKs = 7, kSlots = 8;     // blocks up to order 352, up to 224 real base rows
 __device__ __align__(256) u32x4 g_ptable[kSlots][kMaxTiles * kMaxKs][64];
 
 // Fragments of the base block B = P_b (x) S_{2^fold} of order b 2^fold (fold = 0: the Paley block itself).
@@ -157,12 +157,7 @@ __device__ __align__(256) u32x4 g_ptable[kSlots][kMaxTiles * kMaxKs][64];
 __global__ void __launch_bounds__(64) k_fill_ptable(int slot, int b, int fold, int rows) {
     __shared__ signed char chi[512];
     const int lane = threadIdx.x, q = b - 1, border = b << fold, umask = (1 << fold) - 1;
-    if (b > 1) {
-        for (int i = lane; i < q; i += 64) chi[i] = (i == 0) ? 0 : -1;
-        __syncthreads();
-        for (int i = 1 + lane; i < q; i += 64) chi[(i * i) % q] = 1;
-        __syncthreads();
-    }
+    if (b > 1) PME_FILL_CHI(chi, q, lane, 64);
     const int tile = blockIdx.x / kMaxKs, ks = blockIdx.x % kMaxKs;
     const int ap = tile * 16 + (lane & 15), g = lane >> 4;
     u32x4 pk;
@@ -239,7 +234,7 @@ __device__ __forceinline__ void dma16(const void* sbase, uint32_t voff, uint32_t
 // so the HBM read of token i + 1 runs under the FWHT / quantize / store phase of token i.
 // Most waves a workgroup of this instantiation is launched with (bounds the registers per lane).
 template <int KLOG2, int TPW> constexpr int max_waves() {
-    return ((TPW == 1 && KLOG2 <= 8) || (KLOG2 == 6 && TPW == 2)) ? kMaxWaves : kMaxWaves / 2;
+    return ((TPW == 1 && KLOG2 <= 8) || KLOG2 == 6) ? kMaxWaves : kMaxWaves / 2;
 }
 
 enum { OUT_SYM = 0, OUT_ASYM = 1, OUT_XHAT = 2, OUT_MXFP4 = 3 };   // int4 symmetric / asymmetric codes, fp32 values, MXFP4
@@ -718,9 +713,13 @@ pme_status launch_rotate_mfma(const RotateArgs& in) {
     // few tokens: spread a token over as many waves as it has tiles
     if (a.T < 512 && a.k <= 8) tpw = 1;
     if (g_tpw_override > 0) tpw = g_tpw_override;
-    // The order-312 block at 2^k = 64 (19968 = 312 x 64): 20 column tiles on 10 waves; its fragments
-    // (nt ks KB) do not fit in LDS beside the token and are read from the table in device memory.
-    if (!f32 && a.k == 6 && nt > kMaxWaves && g_tpw_override == 0) return launch_one<6, 2, false, true>(a, ks, (nt + 1) / 2);
+    // The order-312 and order-344 blocks at 2^k = 64 (19968 = 312 x 64, 22016 = 344 x 64): 20 and 22 column
+    // tiles on 10 and 8 waves; their fragments (nt ks KB) do not fit in LDS beside the token and are read
+    // from the table in device memory.
+    if (!f32 && a.k == 6 && nt > kMaxWaves && g_tpw_override == 0) {
+        if (nt <= 2 * kMaxWaves) return launch_one<6, 2, false, true>(a, ks, (nt + 1) / 2);
+        return launch_one<6, 3, false, true>(a, ks, (nt + 2) / 3);
+    }
     const int nwaves = (nt + tpw - 1) / tpw;
     if (nwaves > kMaxWaves) return PME_ERR_UNSUPPORTED_PATH;
     // 2^k = 32 with a block of at most 80: the token is one wave's work and only a few KB

@@ -54,6 +54,8 @@ ROTATE_CASES = [
     # 20 column tiles on 10 waves, P fragments read from device memory
     ("b312_k6", 3, 14336, 19968, "bf16", (GENERIC, MFMA)),
     ("b312_k6_many_tokens_ragged_d", 290, 14000, 19968, "bf16", (MFMA,)),
+    ("b344_k6", 3, 14336, 22016, "bf16", (GENERIC, MFMA)),          # block over GF(7^3), 22 tiles on 8 waves
+    ("b344_k6_many_tokens", 270, 14336, 22016, "bf16", (MFMA,)),
     ("b20_k9", 3, 8192, 10240, "bf16", (GENERIC, MFMA)),
     ("b12_k10", 2, 8192, 12288, "bf16", (GENERIC, MFMA)),
     ("single_token", 1, 2048, 2176, "bf16", (GENERIC, MFMA)),

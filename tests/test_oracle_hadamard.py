@@ -15,7 +15,7 @@ from workloads import make_workload
 
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 ORDERS = (80, 2176, 8704, 8448, 15360)
-BASES = (12, 20, 60, 68, 72, 132, 140, 152, 312)
+BASES = (12, 20, 60, 68, 72, 132, 140, 152, 312, 344)
 
 
 def _signs(line):
@@ -72,9 +72,45 @@ def test_paley_block_is_hadamard(b):
     assert np.all(np.diag(P) == 1)
     S = P - np.eye(b, dtype=np.int64)
     assert np.array_equal(S, -S.T)
-    # the Jacobsthal part is circulant: Q[i][j] depends on (i - j) mod q only
     Q = S[1:, 1:]
-    assert np.array_equal(Q, np.roll(np.roll(Q, 1, axis=0), 1, axis=1))
+    if b != 344:
+        # over a prime field the Jacobsthal part is circulant: Q[i][j] depends on (i - j) mod q only
+        assert np.array_equal(Q, np.roll(np.roll(Q, 1, axis=0), 1, axis=1))
+    else:
+        # over GF(7^3) it depends on the field difference x_i - x_j only
+        from oracle.hadamard import gf343_sub
+        q = b - 1
+        diff = np.array([[gf343_sub(i, j) for j in range(q)] for i in range(q)])
+        assert np.array_equal(Q, Q[:, 0][diff])
+
+
+def test_gf343_is_a_field_of_order_343():
+    from oracle.hadamard import gf343_mul, gf343_sub, gf343_quadratic_character
+    # the modulus t^3 + t + 1 has no root in GF(7): a cubic without roots is irreducible
+    assert all((t ** 3 + t + 1) % 7 != 0 for t in range(7))
+    t, t2 = 7, 49                                  # element numbers of t and t^2
+    assert gf343_mul(t, t) == t2
+    assert gf343_mul(t, t2) == 6 + 6 * 7           # t^3 = -t - 1 = 6 + 6 t
+    assert gf343_mul(t2, t2) == 6 * 7 + 6 * 49     # t^4 = -t^2 - t
+    assert gf343_sub(0, 1) == 6 and gf343_sub(3, 3) == 0 and gf343_sub(7, 8) == 6
+    # no zero divisors, and x -> x y is a bijection for y != 0 (checked for a few y)
+    for y in (1, 2, 7, 50, 342):
+        assert sorted(gf343_mul(x, y) for x in range(343)) == list(range(343))
+    # the multiplicative group has order 342: x^342 = 1; a generator exists (t + 1 or another small element)
+    def power(x, n):
+        r = 1
+        while n:
+            if n & 1:
+                r = gf343_mul(r, x)
+            x = gf343_mul(x, x)
+            n >>= 1
+        return r
+    assert all(power(x, 342) == 1 for x in range(1, 343))
+    chi = gf343_quadratic_character()
+    assert chi[0] == 0 and int((chi == 1).sum()) == 171 and int((chi == -1).sum()) == 171
+    # Euler's criterion: chi(x) = x^((q-1)/2), and -1 is a non-square since q = 3 (mod 4)
+    assert all((power(x, 171) == 1) == (chi[x] == 1) for x in range(1, 343))
+    assert chi[gf343_sub(0, 1)] == -1
 
 
 def test_paley_rejects_bad_orders():
@@ -100,7 +136,8 @@ def test_factor_order_gives_the_workload_factorisations():
     assert oracle.factor_order(12288) == (12, 10)
     assert oracle.factor_order(18432) == (72, 8)
     assert oracle.factor_order(19968) == (312, 6)
-    for bad in (7, 100, 22016):
+    assert oracle.factor_order(22016) == (344, 6)
+    for bad in (7, 100, 11264):
         with pytest.raises(ValueError):
             oracle.factor_order(bad)
 
