@@ -129,6 +129,10 @@ def main() -> int:
     ap.add_argument("--probe-copy", action="store_true",
                     help="time the library's plain 1 GiB copy kernel with 5 launches instead of 2 (the known-size "
                          "dispatch that calibrates the profiler's FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--paper-sizes", action="store_true",
+                    help="also time the layer at every expanded size of the paper's Tables 1-2 (down projections of the "
+                         "1B- and 8B-shaped models: 8192 -> 8704 .. 12288 with N = 2048, 14336 -> 15360 .. 22016 with "
+                         "N = 4096; 2048 tokens, random weights quantized by the library's own weight-side call)")
     ap.add_argument("--no-graph", action="store_true",
                     help="time the plain Python loop of library calls instead of a HIP graph replay of it")
     ap.add_argument("--no-probes", action="store_true",
@@ -288,6 +292,33 @@ def main() -> int:
             del wl2, b2
             torch.cuda.empty_cache()
         out["other_workloads"] = others
+    if args.paper_sizes:
+        rows = []
+        for d, N, sizes in ((8192, 2048, (8704, 8960, 9728, 10240, 12288)), (14336, 4096, (15360, 18432, 19968, 22016))):
+            T = 2048
+            xs = (torch.randn((T, d), device="cuda") * (1 + 20 * (torch.rand(d, device="cuda") < 0.01))).to(torch.bfloat16)
+            wt = torch.randn((N, d), device="cuda").to(torch.bfloat16)
+            for d_e in sizes:
+                qw_, sw_ = pme.expand_quantize_weights(wt, d_e)
+                y_ = torch.empty((T, N), dtype=torch.bfloat16, device="cuda")
+                ws_ = torch.empty((pme.workspace_bytes(T, d, d_e, N),), dtype=torch.uint8, device="cuda")
+                qx_ = torch.empty((T, d_e // 2), dtype=torch.uint8, device="cuda")
+                sx_ = torch.empty((T,), dtype=torch.float32, device="cuda")
+                layer_ = lambda: pme.expanded_linear(xs, d_e, qw_, sw_, y_, ws_)
+                rot_ = lambda: pme.hadamard_expand_quant(xs, d_e, qx_, sx_)
+                for _ in range(5):
+                    layer_()
+                rot_()
+                tl = _graph_ms(layer_, 30) or _event_ms(layer_, 30, 3)
+                tr = _graph_ms(rot_, 30) or _event_ms(rot_, 30, 3)
+                b_, k_ = pme.factor_order(d_e)
+                rows.append({"T": T, "d": d, "d_e": d_e, "N": N, "ratio": round(d_e / d, 3), "order": f"{b_} x 2^{k_}",
+                             "layer_us": tl * 1e3, "rotate_quant_us": tr * 1e3,
+                             "layer_tops": 2.0 * T * d_e * N / (tl * 1e-3) / 1e12})
+                del qw_, sw_, y_, ws_, qx_, sx_
+            del xs, wt
+            torch.cuda.empty_cache()
+        out["paper_sizes"] = rows
     if args.mxfp4:
         wt = torch.randn((sp.N, sp.d), device="cuda").to(torch.bfloat16)     # any weights: timing only
         qw4, ew4 = pme.hadamard_expand_quant_mxfp4(wt, sp.d_e)
