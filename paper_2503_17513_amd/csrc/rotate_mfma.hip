@@ -713,12 +713,18 @@ pme_status launch_rotate_mfma(const RotateArgs& in) {
     // few tokens: spread a token over as many waves as it has tiles
     if (a.T < 512 && a.k <= 8) tpw = 1;
     if (g_tpw_override > 0) tpw = g_tpw_override;
-    // The order-312 and order-344 blocks at 2^k = 64 (19968 = 312 x 64, 22016 = 344 x 64): 20 and 22 column
-    // tiles on 10 and 8 waves; their fragments (nt ks KB) do not fit in LDS beside the token and are read
-    // from the table in device memory.
-    if (!f32 && a.k == 6 && nt > kMaxWaves && g_tpw_override == 0) {
-        if (nt <= 2 * kMaxWaves) return launch_one<6, 2, false, true>(a, ks, (nt + 1) / 2);
-        return launch_one<6, 3, false, true>(a, ks, (nt + 2) / 3);
+    // P fragments read from the table in device memory instead of LDS:
+    //  * 2^k = 64 with 8 tiles or more (orders 132 .. 152: 8448, 8960, 9728): staging nt ks KB of fragments
+    //    leaves room for only two workgroups per compute unit; without it the kernel measured 18 % faster;
+    //  * the order-312 and order-344 blocks (19968 = 312 x 64, 22016 = 344 x 64): 20 and 22 column tiles on 10
+    //    and 8 waves, about 150 KB of fragments that do not fit in LDS beside the token at all;
+    //  * 2^k = 128 (8704): 4 % faster.
+    if (!f32 && g_tpw_override == 0) {
+        if (a.k == 6 && nt >= 8) {
+            if (nt <= 2 * kMaxWaves) return launch_one<6, 2, false, true>(a, ks, (nt + 1) / 2);
+            return launch_one<6, 3, false, true>(a, ks, (nt + 2) / 3);
+        }
+        if (a.k == 7 && tpw == 2) return launch_one<7, 2, false, true>(a, ks, (nt + 1) / 2);
     }
     const int nwaves = (nt + tpw - 1) / tpw;
     if (nwaves > kMaxWaves) return PME_ERR_UNSUPPORTED_PATH;
