@@ -126,6 +126,8 @@ def main() -> int:
     ap.add_argument("--stages", action="store_true", help="also time each stage and every other workload")
     ap.add_argument("--mxfp4", action="store_true",
                     help="also time the MXFP4 variant of the layer (the paper's second quantization setting)")
+    ap.add_argument("--asym", action="store_true",
+                    help="also time the layer with per-token asymmetric int4 activations (the paper's W4A4 setting)")
     ap.add_argument("--probe-copy", action="store_true",
                     help="time the library's plain 1 GiB copy kernel with 5 launches instead of 2 (the known-size "
                          "dispatch that calibrates the profiler's FETCH_SIZE / WRITE_SIZE counters)")
@@ -319,6 +321,19 @@ def main() -> int:
             del xs, wt
             torch.cuda.empty_cache()
         out["paper_sizes"] = rows
+    if args.asym:
+        wsum = pme.weight_rowsum(b["qw"])
+        zx = torch.empty((sp.T,), dtype=torch.int32, device="cuda")
+        layer_a = lambda: pme.expanded_linear_asym(b["x"], sp.d_e, b["qw"], b["sw"], wsum, b["y"], b["ws"])
+        rot_a = lambda: pme.hadamard_expand_quant_asym(b["x"], sp.d_e, b["qx"], b["sx"], zx)
+        gemm_a = lambda: pme.w4a4_gemm_asym(b["qx"], b["sx"], zx, b["qw"], b["sw"], wsum, b["y"])
+        for f in (layer_a, rot_a, gemm_a):
+            for _ in range(3):
+                f()
+        it = max(20, args.steps)
+        t_l, t_r, t_g = (_graph_ms(f, it) or _event_ms(f, it, 5) for f in (layer_a, rot_a, gemm_a))
+        out["asym"] = {"layer_us": t_l * 1e3, "layer_tops": ops / (t_l * 1e-3) / 1e12, "rotate_quant_us": t_r * 1e3,
+                       "gemm_us": t_g * 1e3, "gemm_tops": ops / (t_g * 1e-3) / 1e12}
     if args.mxfp4:
         wt = torch.randn((sp.N, sp.d), device="cuda").to(torch.bfloat16)     # any weights: timing only
         qw4, ew4 = pme.hadamard_expand_quant_mxfp4(wt, sp.d_e)

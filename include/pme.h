@@ -121,6 +121,16 @@ pme_status pme_expanded_linear(const void* x, pme_dtype xt, int64_t T, int64_t d
                                void* stream);
 
 /*
+ * The same with the paper's activation quantizer (Section 4: per-token asymmetric int4):
+ * pme_hadamard_expand_quant_asym followed by pme_w4a4_gemm_asym; wsum DEVICE [N] from pme_weight_rowsum.
+ * Codes, scales and zero points pass through `workspace` (same size and alignment as above).
+ */
+pme_status pme_expanded_linear_asym(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                                    int64_t d_e, const uint8_t* qw, const float* sw, const int32_t* wsum,
+                                    int64_t N, void* y_bf16, int64_t ldy, void* workspace,
+                                    size_t workspace_bytes, void* stream);
+
+/*
  * Offline weight side (Section 3: W_hat = H_hat^T W; Section 4: per-channel symmetric int4, here by
  * round-to-nearest): expands and quantizes a weight matrix into the qw / sw operands of pme_w4a4_gemm.
  *   wt  DEVICE [N, d] row-major (one row of d input weights per output channel, i.e. W^T of the paper's
@@ -156,7 +166,7 @@ pme_status pme_expanded_linear_mxfp4(const void* x, pme_dtype xt, int64_t T, int
                                      void* y_bf16, int64_t ldy, void* workspace, size_t workspace_bytes,
                                      void* stream);
 
-/* Bytes of workspace pme_expanded_linear and pme_expanded_linear_mxfp4 need (0 on invalid sizes). */
+/* Bytes of workspace the pme_expanded_linear* calls need (one size serves all three; 0 on invalid sizes). */
 size_t pme_workspace_bytes(int64_t T, int64_t d, int64_t d_e, int64_t N);
 
 /* ---- parity / debug exports ---- */

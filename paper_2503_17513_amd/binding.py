@@ -16,7 +16,7 @@ F32, BF16 = 0, 1
 # Every symbol include/pme.h declares.
 EXPORTS = ("pme_hadamard_expand_quant", "pme_expand_quantize_weights", "pme_hadamard_expand_quant_mxfp4",
            "pme_mxfp4_gemm", "pme_expanded_linear_mxfp4", "pme_hadamard_expand_quant_asym", "pme_w4a4_gemm", "pme_w4a4_gemm_asym",
-           "pme_weight_rowsum", "pme_expanded_linear", "pme_workspace_bytes", "pme_hadamard_expand_f32",
+           "pme_weight_rowsum", "pme_expanded_linear", "pme_expanded_linear_asym", "pme_workspace_bytes", "pme_hadamard_expand_f32",
            "pme_w4a4_gemm_i32", "pme_factor_order", "pme_base_block", "pme_probe_copy", "pme_probe_mfma", "pme_set_path", "pme_set_gemm_tile",
            "pme_get_path", "pme_status_string", "pme_version")
 
@@ -52,6 +52,7 @@ def lib() -> C.CDLL:
     L.pme_w4a4_gemm_i32.argtypes = [vp, vp, i64, i64, i64, vp, vp]
     L.pme_weight_rowsum.argtypes = [vp, i64, i64, vp, vp]
     L.pme_expanded_linear.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i64, vp, i64, vp, sz, vp]
+    L.pme_expanded_linear_asym.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp, i64, vp, i64, vp, sz, vp]
     L.pme_workspace_bytes.argtypes = [i64, i64, i64, i64]
     L.pme_workspace_bytes.restype = sz
     L.pme_factor_order.argtypes = [i64, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
@@ -192,13 +193,17 @@ def expanded_linear_mxfp4(x, d_e: int, qw, ew, y: torch.Tensor | None = None, wo
     return y
 
 
-def hadamard_expand_quant_asym(x: torch.Tensor, d_e: int):
+def hadamard_expand_quant_asym(x: torch.Tensor, d_e: int, qx: torch.Tensor | None = None,
+                               sx: torch.Tensor | None = None, zx: torch.Tensor | None = None):
     T, d, ldx = _rows(x)
-    qx = torch.empty((T, d_e // 2), dtype=torch.uint8, device=x.device)
-    sx = torch.empty((T,), dtype=torch.float32, device=x.device)
-    zx = torch.empty((T,), dtype=torch.int32, device=x.device)
-    _check(lib().pme_hadamard_expand_quant_asym(_dev(x, "x"), _dtype_code(x), T, d, ldx, d_e, qx.data_ptr(),
-                                                sx.data_ptr(), zx.data_ptr(), _stream()),
+    if qx is None:
+        qx = torch.empty((T, d_e // 2), dtype=torch.uint8, device=x.device)
+    if sx is None:
+        sx = torch.empty((T,), dtype=torch.float32, device=x.device)
+    if zx is None:
+        zx = torch.empty((T,), dtype=torch.int32, device=x.device)
+    _check(lib().pme_hadamard_expand_quant_asym(_dev(x, "x"), _dtype_code(x), T, d, ldx, d_e, _dev(qx, "qx"),
+                                                _dev(sx, "sx"), _dev(zx, "zx"), _stream()),
            "pme_hadamard_expand_quant_asym")
     return qx, sx, zx
 
@@ -229,11 +234,33 @@ def w4a4_gemm(qx, sx, qw, sw, y: torch.Tensor | None = None) -> torch.Tensor:
     return y
 
 
-def w4a4_gemm_asym(qx, sx, zx, qw, sw, wsum) -> torch.Tensor:
+def w4a4_gemm_asym(qx, sx, zx, qw, sw, wsum, y: torch.Tensor | None = None) -> torch.Tensor:
     T, d_e, N = _gemm_shapes(qx, qw)
-    y = torch.empty((T, N), dtype=torch.bfloat16, device=qx.device)
-    _check(lib().pme_w4a4_gemm_asym(qx.data_ptr(), sx.data_ptr(), zx.data_ptr(), qw.data_ptr(), sw.data_ptr(),
-                                    wsum.data_ptr(), T, d_e, N, y.data_ptr(), N, _stream()), "pme_w4a4_gemm_asym")
+    if y is None:
+        y = torch.empty((T, N), dtype=torch.bfloat16, device=qx.device)
+    _check(lib().pme_w4a4_gemm_asym(_dev(qx, "qx"), _dev(sx, "sx"), _dev(zx, "zx"), _dev(qw, "qw"), _dev(sw, "sw"),
+                                    _dev(wsum, "wsum"), T, d_e, N, _dev(y, "y"),
+                                    y.stride(0) if T > 1 else max(y.stride(0), N), _stream()), "pme_w4a4_gemm_asym")
+    return y
+
+
+def expanded_linear_asym(x, d_e: int, qw, sw, wsum, y: torch.Tensor | None = None,
+                         workspace: torch.Tensor | None = None):
+    """The layer with per-token asymmetric int4 activations (the paper's W4A4 setting)."""
+    T, d, ldx = _rows(x)
+    N = qw.shape[0]
+    if qw.shape[1] * 2 != d_e:
+        raise ValueError("qw must be [N, d_e / 2]")
+    need = workspace_bytes(T, d, d_e, N)
+    if workspace is None:
+        workspace = torch.empty((max(need, 256),), dtype=torch.uint8, device=x.device)
+    if y is None:
+        y = torch.empty((T, N), dtype=torch.bfloat16, device=x.device)
+    _check(lib().pme_expanded_linear_asym(_dev(x, "x"), _dtype_code(x), T, d, ldx, d_e, _dev(qw, "qw"), _dev(sw, "sw"),
+                                          _dev(wsum, "wsum"), N, _dev(y, "y"),
+                                          y.stride(0) if T > 1 else max(y.stride(0), N), _dev(workspace, "workspace"),
+                                          workspace.numel() * workspace.element_size(), _stream()),
+           "pme_expanded_linear_asym")
     return y
 
 

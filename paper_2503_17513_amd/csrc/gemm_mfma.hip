@@ -85,7 +85,7 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     constexpr int STAGE = ROWS * RB;
     constexpr int NSUB = RB / 32;                 // sub-steps of 64 codes per K step
     constexpr int SLAB = 32 * WN * 2;             // epilogue: one 32-token slab of the wave tile in bf16
-    static_assert(NW * SLAB + ROWS * 4 <= NSTAGE * STAGE, "epilogue staging must fit in the K-loop stages");
+    static_assert(NW * SLAB + ROWS * 8 <= NSTAGE * STAGE, "epilogue staging must fit in the K-loop stages");
     static_assert(NSTAGE == 2 || NSTAGE == 3, "two or three stages");
 
     extern __shared__ __align__(1024) unsigned char smem[];      // NSTAGE stages
@@ -125,6 +125,17 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             pre[q] = 0.f;
             if (idx < BM) pre[q] = sx[min(m0 + idx, T - 1)] * (1.f / 256.f);
             else if (idx < ROWS) pre[q] = sw[min(n0 + idx - BM, N - 1)];
+        }
+    }
+    // asymmetric codes: the tokens' zero points and the channels' weight row sums travel the same way
+    int prez[PRE];
+    if constexpr (MODE == MODE_ASYM) {
+#pragma unroll
+        for (int q = 0; q < PRE; ++q) {
+            const int idx = tid + NT * q;
+            prez[q] = 0;
+            if (idx < BM) prez[q] = zx[min(m0 + idx, T - 1)];
+            else if (idx < ROWS) prez[q] = wsum[min(n0 + idx - BM, N - 1)];
         }
     }
     const uint32_t lds0 = (uint32_t)(uintptr_t)(PME_AS3 unsigned char*)smem;
@@ -349,10 +360,14 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
         // all waves are past the last barrier of the K loop: the stages are free for staging
         unsigned char* slab = smem + (size_t)wave * SLAB;
         float* sc = reinterpret_cast<float*>(smem + (size_t)NW * SLAB);     // [BM] token scales, [BN] channel scales
+        int* zc = reinterpret_cast<int*>(sc + ROWS);                        // [BM] zero points, [BN] weight row sums
 #pragma unroll
         for (int q = 0; q < PRE; ++q) {
             const int idx = tid + NT * q;
-            if (idx < ROWS) sc[idx] = pre[q];
+            if (idx < ROWS) {
+                sc[idx] = pre[q];
+                if constexpr (MODE == MODE_ASYM) zc[idx] = prez[q];
+            }
         }
         lds_barrier();
         f32x4 swv[FN][4];
@@ -364,8 +379,7 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
                 swv[j][eg] = *reinterpret_cast<const f32x4*>(sc + BM + wn * WN + 32 * j + 8 * eg + 4 * fk);
                 if (MODE == MODE_ASYM) {
 #pragma unroll
-                    for (int q = 0; q < 4; ++q)
-                        wsv[j][eg][q] = wsum[min(n0 + wn * WN + 32 * j + 8 * eg + 4 * fk + q, N - 1)];
+                    for (int q = 0; q < 4; ++q) wsv[j][eg][q] = zc[BM + wn * WN + 32 * j + 8 * eg + 4 * fk + q];
                 }
             }
         uint16_t* y = static_cast<uint16_t*>(out);
@@ -374,7 +388,7 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             const int t = min(m0 + wm * WM + 32 * i + frow, T - 1);
             const float sxs = sc[wm * WM + 32 * i + frow];
             int zoff = 0;
-            if (MODE == MODE_ASYM) zoff = (zx[t] - 8) * 256;
+            if (MODE == MODE_ASYM) zoff = (zc[wm * WM + 32 * i + frow] - 8) * 256;
 #pragma unroll
             for (int j = 0; j < FN; ++j)
 #pragma unroll

@@ -159,9 +159,10 @@ pme_status pme_weight_rowsum(const uint8_t* qw, int64_t N, int64_t d_e, int32_t*
 size_t pme_workspace_bytes(int64_t T, int64_t d, int64_t d_e, int64_t N) {
     (void)N;
     if (T < 0 || d <= 0 || d_e <= 0 || d > d_e || (d_e & 1)) return 0;
-    // packed codes [T, d_e/2], then per-token scales [T] fp32 or MXFP4 scale bytes [T, d_e/32]; 256-byte aligned
+    // packed codes [T, d_e/2], then per-token scales [T] fp32 or MXFP4 scale bytes [T, d_e/32], then the
+    // zero points [T] int32 of the asymmetric variant; each 256-byte aligned
     const size_t scales = std::max((size_t)T * sizeof(float), (size_t)T * (size_t)(d_e / 32));
-    return round_up((size_t)T * (size_t)(d_e / 2), 256) + round_up(scales, 256);
+    return round_up((size_t)T * (size_t)(d_e / 2), 256) + round_up(scales, 256) + round_up((size_t)T * sizeof(int32_t), 256);
 }
 
 pme_status pme_expanded_linear(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
@@ -185,6 +186,32 @@ pme_status pme_expanded_linear(const void* x, pme_dtype xt, int64_t T, int64_t d
     s = run_rotate(ra);
     if (s != PME_OK) return s;
     pme::GemmArgs ga{qx, qw, sx, sw, nullptr, nullptr, T, d_e, N, y_bf16, ldy, false, (hipStream_t)stream};
+    return run_gemm(ga);
+}
+
+pme_status pme_expanded_linear_asym(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                                    int64_t d_e, const uint8_t* qw, const float* sw, const int32_t* wsum,
+                                    int64_t N, void* y_bf16, int64_t ldy, void* workspace,
+                                    size_t workspace_bytes, void* stream) {
+    int b, k;
+    pme_status s = check_rotate(x, xt, T, d, ldx, d_e, &b, &k);
+    if (s != PME_OK) return s;
+    if (N < 0 || N > 0x7FFFFFFF || ldy < N) return PME_ERR_SHAPE;
+    if (T > 0 && N > 0 && (!qw || !sw || !wsum || !y_bf16)) return PME_ERR_NULL;
+    if (!aligned(qw, 4) || !aligned(sw, 4) || !aligned(wsum, 4) || !aligned(y_bf16, 2)) return PME_ERR_ALIGN;
+    const size_t need = pme_workspace_bytes(T, d, d_e, N);
+    if (T > 0 && !workspace) return PME_ERR_NULL;
+    if (!aligned(workspace, 256)) return PME_ERR_ALIGN;
+    if (workspace_bytes < need) return PME_ERR_WORKSPACE;
+    if (T == 0 || N == 0) return PME_OK;
+    uint8_t* qx = static_cast<uint8_t*>(workspace);
+    const size_t scales = std::max((size_t)T * sizeof(float), (size_t)T * (size_t)(d_e / 32));
+    float* sx = reinterpret_cast<float*>(qx + round_up((size_t)T * (size_t)(d_e / 2), 256));
+    int32_t* zx = reinterpret_cast<int32_t*>(reinterpret_cast<uint8_t*>(sx) + round_up(scales, 256));
+    pme::RotateArgs ra{x, xt, T, d, ldx, d_e, b, k, qx, sx, zx, nullptr, nullptr, (hipStream_t)stream};
+    s = run_rotate(ra);
+    if (s != PME_OK) return s;
+    pme::GemmArgs ga{qx, qw, sx, sw, zx, wsum, T, d_e, N, y_bf16, ldy, false, (hipStream_t)stream};
     return run_gemm(ga);
 }
 

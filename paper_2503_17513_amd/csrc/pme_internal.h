@@ -165,15 +165,14 @@ __host__ __device__ inline int gf_square(int q, int i) {
     p0 = ((p0 % 7) + 7) % 7; p1 = ((p1 % 7) + 7) % 7; p2 = ((p2 % 7) + 7) % 7;
     return p0 + 7 * p1 + 49 * p2;
 }
-// Quadratic character table of GF(q): chi[0] = 0, +1 at the non-zero squares, -1 elsewhere; threads
-// tid, tid + nthreads, ... of a workgroup fill it together (two passes with a barrier between them).
-#define PME_FILL_CHI(chi, q, tid, nthreads)                                          \
-    do {                                                                             \
-        for (int i_ = (tid); i_ < (q); i_ += (nthreads)) (chi)[i_] = (i_ == 0) ? 0 : -1; \
-        __syncthreads();                                                             \
-        for (int i_ = 1 + (tid); i_ < (q); i_ += (nthreads)) (chi)[gf_square((q), i_)] = 1; \
-        __syncthreads();                                                             \
-    } while (0)
+// Quadratic character table of GF(q): chi[0] = 0, +1 at the non-zero squares, -1 elsewhere.  Called by every
+// thread of a workgroup (thread tid of nthreads); the table is complete when the call returns.
+__device__ inline void fill_quadratic_character(signed char* chi, int q, int tid, int nthreads) {
+    for (int i = tid; i < q; i += nthreads) chi[i] = (i == 0) ? 0 : -1;
+    __syncthreads();
+    for (int i = 1 + tid; i < q; i += nthreads) chi[gf_square(q, i)] = 1;
+    __syncthreads();
+}
 
 // Entry (a, a') of the Paley block P = I + [[0, 1^T], [-1, Q]], Q[i][j] = chi(x_i - x_j), block index a >= 1
 // standing for field element a - 1.

@@ -48,7 +48,7 @@ k_rotate_generic(const InT* __restrict__ x, int64_t ldx, int d, int d_e, int b, 
     const int q = b - 1;
     const InT* xr = x + t * ldx;
 
-    if (b > 1) PME_FILL_CHI(chi, q, tid, kThreads);
+    if (b > 1) fill_quadratic_character(chi, q, tid, kThreads);
 
     const int rows = (d + n - 1) >> k;   // base rows that hold at least one real input
     for (int idx = tid; idx < d_e; idx += kThreads) {

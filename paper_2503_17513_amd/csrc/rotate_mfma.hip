@@ -157,7 +157,7 @@ __device__ __align__(256) u32x4 g_ptable[kSlots][kMaxTiles * kMaxKs][64];
 __global__ void __launch_bounds__(64) k_fill_ptable(int slot, int b, int fold, int rows) {
     __shared__ signed char chi[512];
     const int lane = threadIdx.x, q = b - 1, border = b << fold, umask = (1 << fold) - 1;
-    if (b > 1) PME_FILL_CHI(chi, q, lane, 64);
+    if (b > 1) fill_quadratic_character(chi, q, lane, 64);
     const int tile = blockIdx.x / kMaxKs, ks = blockIdx.x % kMaxKs;
     const int ap = tile * 16 + (lane & 15), g = lane >> 4;
     u32x4 pk;
@@ -369,7 +369,7 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
     };
     const int l4 = (lane >> 4) & 1, l5 = lane >> 5;
     const int c0 = run_start<KLOG2>(l4, l5);
-    const float g7 = (float)(gamma / 7.0);
+    const float g7 = (float)(gamma / 7.0), g15 = (float)(gamma / 15.0);
 
     for (; t < T; t += t_step) {
         if constexpr (F32IN) {
@@ -512,9 +512,9 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
 #pragma unroll
             for (int ti = 0; ti < TPW; ++ti)
 #pragma unroll
-                for (int i = 0; i < NREG; ++i) {
-                    hi = fmaxf(hi, v[ti][i]);
-                    lo = fminf(lo, v[ti][i]);
+                for (int i = 0; i < NREG; i += 2) {       // v_max3_f32 / v_min3_f32: one instruction per element in all
+                    hi = __builtin_fmaxf(__builtin_fmaxf(hi, v[ti][i]), v[ti][i + 1]);
+                    lo = __builtin_fminf(__builtin_fminf(lo, v[ti][i]), v[ti][i + 1]);
                 }
             lo = wave_min(lo);
         } else {
@@ -544,9 +544,11 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
             if (tid == 0) sx[t] = s;
         } else {
             if (hi > lo) {
-                s = (float)(((double)hi - (double)lo) * gamma / 15.0);
-                rinv = (float)(gamma / (double)s);
-                z = (int)rint(-(double)lo * gamma / (double)s);
+                // fp32 like the symmetric case: scale = range * fp32(gamma / 15), codes from u * (15 / range)
+                const float range = hi - lo;
+                s = range * g15;
+                rinv = 15.f * __builtin_amdgcn_rcpf(range);
+                z = (int)__builtin_rintf(-lo * rinv);
                 z = min(15, max(0, z));
             }
             if (tid == 0) { sx[t] = s; zx[t] = z; }
@@ -575,15 +577,17 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
                     }
                     words[wd] = (accw - kCsum) ^ 0x88888888u;
                 } else {
+                    // the zero point rides in the rounding constant (rne(u rinv + z) = rne(u rinv) + z), the clamp
+                    // to [0, 15] is one median-of-three on the float, then the same Horner packing
+                    const float cz = 12582912.f + (float)z;
                     uint32_t accw = 0;
 #pragma unroll
                     for (int nb = 7; nb >= 0; --nb) {
-                        const float f = __builtin_fmaf(v[ti][L::reg_of_run_pos(wd * 8 + nb)], rinv, 12582912.f);
-                        int code = (int)(__float_as_uint(f) - kC) + z;
-                        code = min(15, max(0, code));
-                        accw = (accw << 4) + (uint32_t)code;
+                        float f = __builtin_fmaf(v[ti][L::reg_of_run_pos(wd * 8 + nb)], rinv, cz);
+                        f = __builtin_amdgcn_fmed3f(f, 12582912.f, 12582927.f);
+                        accw = (accw << 4) + __float_as_uint(f);
                     }
-                    words[wd] = accw;
+                    words[wd] = accw - kCsum;
                 }
             }
             if (ap < b) {

@@ -101,8 +101,9 @@ def test_gemm_argument_errors():
 def test_expanded_linear_argument_errors():
     f = pme.lib().pme_expanded_linear
     need = pme.workspace_bytes(4, 64, 80, 8)
-    assert need == 256 + 256
-    assert pme.workspace_bytes(2048, 2048, 2176, 3072) == 2048 * 1088 + 2048 * 68   # codes + MXFP4 scale bytes
+    assert need == 256 + 256 + 256
+    # codes + MXFP4 scale bytes (the larger of the two scale kinds) + zero points of the asymmetric variant
+    assert pme.workspace_bytes(2048, 2048, 2176, 3072) == 2048 * 1088 + 2048 * 68 + 2048 * 4
     assert pme.workspace_bytes(4, 81, 80, 8) == 0
 
     def call(x=FAKE, xt=1, T=4, d=64, ldx=64, d_e=80, qw=FAKE, sw=FAKE, N=8, y=FAKE, ldy=8, ws=FAKE, wsb=need):
@@ -152,6 +153,22 @@ def test_mxfp4_and_weight_argument_errors():
     assert a(FAKE, FAKE, FAKE, FAKE, FAKE, None, 4, 80, 8, FAKE, 8, None) == NULL
     q = L.pme_hadamard_expand_quant_asym
     assert q(FAKE, 1, 4, 64, 64, 80, FAKE, FAKE, None, None) == NULL
+
+
+def test_expanded_linear_asym_argument_errors():
+    f = pme.lib().pme_expanded_linear_asym
+    need = pme.workspace_bytes(4, 64, 80, 8)
+
+    def call(x=FAKE, xt=1, T=4, d=64, ldx=64, d_e=80, qw=FAKE, sw=FAKE, wsum=FAKE, N=8, y=FAKE, ldy=8, ws=FAKE, wsb=need):
+        return f(x, xt, T, d, ldx, d_e, qw, sw, wsum, N, y, ldy, ws, wsb, None)
+
+    assert call(wsum=None) == NULL
+    assert call(wsum=FAKE + 2) == ALIGN
+    assert call(wsb=need - 1) == WORKSPACE
+    assert call(ws=FAKE + 128) == ALIGN
+    assert call(d_e=11264) == ORDER
+    assert call(ldy=7) == SHAPE
+    assert call(T=0) == OK
 
 
 def test_probe_copy_errors():

@@ -288,6 +288,34 @@ def test_expanded_linear_end_to_end(name, shape):
     assert nflip <= max(1, int(1e-4 * q_gpu.size))
 
 
+@pytest.mark.parametrize("shape", ((300, 2048, 2176, 520), (8, 8192, 8448, 2048), (130, 14336, 15360, 260)))
+def test_expanded_linear_asymmetric_end_to_end(shape):
+    # the paper's own activation quantizer (per-token asymmetric int4) through the fused call
+    T, d, d_e, N = shape
+    wl = make_workload(custom_spec(T, d, d_e, N, act_dist="student_t3", outlier_frac=0.005, outlier_gain=100.0, seed=2))
+    x = wl.x + np.float32(0.125)                  # an offset, so that the zero points are not all mid-range
+    x = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
+    ref = oracle.expanded_linear(x, d_e, wl.qw, wl.sw, asymmetric=True)
+    xd = to_device(x, "bf16")
+    wd = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+    swd = torch.from_numpy(wl.sw).cuda()
+    wsum = pme.weight_rowsum(wd)
+    y = pme.expanded_linear_asym(xd, d_e, wd, swd, wsum)
+    # the fused call equals the chain of its parts, bit for bit
+    qx, sx, zx = pme.hadamard_expand_quant_asym(xd, d_e)
+    y2 = pme.w4a4_gemm_asym(qx, sx, zx, wd, swd, wsum)
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+    # and the chain evaluated by the oracle on the library's codes
+    q_gpu = unpack_gpu(qx, signed=False)
+    y_chain = oracle.dequant_asym_bf16(oracle.int_gemm(q_gpu, wl.qw), sx.cpu().numpy(), zx.cpu().numpy(), wl.qw, wl.sw)
+    check_bf16(y.to(torch.float32).cpu().numpy(), y_chain)
+    same = np.all(q_gpu == ref["qx"], axis=1) & (sx.cpu().numpy() == ref["sx"]) & (zx.cpu().numpy() == ref["zx"])
+    if same.any():
+        check_bf16(y.to(torch.float32).cpu().numpy()[same], ref["y"][same])
+    yf = y.to(torch.float32).cpu().numpy()
+    assert np.linalg.norm(yf - ref["y"]) <= 2e-3 * np.linalg.norm(ref["y"])
+
+
 @pytest.mark.parametrize("d,d_e,N,dtype", ((64, 80, 48, "f32"), (2048, 2176, 300, "f32"), (8192, 8704, 130, "bf16")))
 def test_offline_weight_expansion_and_whole_layer_from_real_weights(d, d_e, N, dtype):
     # W_hat = H_hat^T W then per-channel round-to-nearest int4 (Sections 3 and 4), on the GPU, against the
