@@ -66,14 +66,18 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
     return __builtin_bit_cast(uint32_t, p);
 }
 
-// BM x BN output tile, WGM x WGN waves, RB packed bytes (2 RB codes) per row and K step, NSTAGE LDS stages.
-template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE, int MODE>
-__global__ void __launch_bounds__(64 * WGM * WGN)
+// BM x BN output tile, WGM x WGN x KS waves, RB packed bytes (2 RB codes) per row and K step, NSTAGE LDS stages.
+// KS = 2: two waves share every wave tile and split each K step's sub-steps between them (the first half and
+// the second half), so that a compute unit's four waves hold tiles twice as large -- half the fragment reads
+// and unpack arithmetic per matrix instruction -- where the output only gives each compute unit a small tile;
+// the two partial accumulators are added through LDS before the epilogue.
+template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE, int MODE, int KS = 1>
+__global__ void __launch_bounds__(64 * WGM * WGN * KS)
 k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             const float* __restrict__ sx, const float* __restrict__ sw,
             const int32_t* __restrict__ zx, const int32_t* __restrict__ wsum,
             int T, int N, int kb, void* __restrict__ out, int64_t ldo, int tiles_m, int tiles_n, int xcd_gm, int vec_store) {
-    constexpr int NW = WGM * WGN;
+    constexpr int NW = WGM * WGN * KS;
     constexpr int WM = BM / WGM, WN = BN / WGN, FM = WM / 32, FN = WN / 32;
     constexpr int ROWS = BM + BN;
     constexpr int CPR = RB / 16;                  // 16-byte chunks per row
@@ -83,7 +87,11 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     // on it); when the blocks do not divide evenly the surplus instructions repeat an earlier block.
     constexpr int CH = (BLKS + NW - 1) / NW;
     constexpr int STAGE = ROWS * RB;
-    constexpr int NSUB = RB / 32;                 // sub-steps of 64 codes per K step
+    constexpr int NSUBG = RB / 32;                // sub-steps of 64 codes per K step
+    constexpr int NSUB = NSUBG / KS;              // ... of which a wave computes this many
+    static_assert(KS == 1 || (KS == 2 && NSUB >= 2 && FM % 2 == 0), "K split: two halves of at least two sub-steps");
+    constexpr int XCH = (KS == 2) ? (FM / 2) * FN * 16 * 256 : 0;     // bytes a wave hands to its partner
+    static_assert(NW * XCH <= NSTAGE * STAGE, "the partial accumulators are exchanged through the K-loop stages");
     constexpr int SLAB = 32 * WN * 2;             // epilogue: one 32-token slab of the wave tile in bf16
     static_assert(NW * SLAB + ROWS * 8 <= NSTAGE * STAGE, "epilogue staging must fit in the K-loop stages");
     static_assert(NSTAGE == 2 || NSTAGE == 3, "two or three stages");
@@ -91,7 +99,9 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     extern __shared__ __align__(1024) unsigned char smem[];      // NSTAGE stages
 
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / WGN, wn = wave % WGN;
+    const int kh = wave / (WGM * WGN);            // which half of every K step (0 when KS = 1)
+    const int wm = (wave % (WGM * WGN)) / WGN, wn = wave % WGN;
+    const int s_off = kh * NSUB;                  // first sub-step of this wave within a K step
 
     int tm, tn;
     xcd_tile((int)blockIdx.x, tiles_m, tiles_n, xcd_gm, tm, tn);     // compact tile block per XCD
@@ -167,18 +177,19 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
 
     const int frow = lane & 31, fk = lane >> 5;
-    // LDS byte offsets of this lane's fragments within a stage for sub-step 0; sub-step s reads logical
-    // chunk 2 s + fk, i.e. position (2 s + fk) ^ swz(r) = (fk ^ swz(r)) ^ 2 s.
+    // LDS byte offsets of this lane's fragments within a stage for the wave's first sub-step; sub-step s reads
+    // logical chunk 2 s + fk, i.e. position (2 s + fk) ^ swz(r) = (fk ^ swz(r)) ^ 2 s (s_off is 0 or a power
+    // of two above the wave's own sub-step bits, so it can be folded in here).
     int aoff[FM], boff[FN];
 #pragma unroll
     for (int i = 0; i < FM; ++i) {
         const int r = wm * WM + 32 * i + frow;
-        aoff[i] = r * RB + ((fk ^ swz<RB>(r)) << 4);
+        aoff[i] = (r * RB + ((fk ^ swz<RB>(r)) << 4)) ^ (s_off << 5);
     }
 #pragma unroll
     for (int j = 0; j < FN; ++j) {
         const int r = BM + wn * WN + 32 * j + frow;
-        boff[j] = r * RB + ((fk ^ swz<RB>(r)) << 4);
+        boff[j] = (r * RB + ((fk ^ swz<RB>(r)) << 4)) ^ (s_off << 5);
     }
     struct Frags { u32x4 a[FM], b[FN]; };                         // 32 packed codes per lane and fragment
     struct Unpacked { i32x4 alo[FM], ahi[FM], blo[FN], bhi[FN]; };   // the same as int8 x 16 MFMA operands
@@ -332,9 +343,9 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
         const unsigned char* scur = smem + cur * STAGE;
 #pragma unroll
         for (int s = 0; s < NSUB; ++s) {
-            if (s < tail_sub) {                              // wave-uniform
-                if (s + 2 < tail_sub) load_frags(raw[s & 1], scur, s + 2);
-                if (s + 1 < tail_sub) unpack(raw[(s + 1) & 1], unp[(s + 1) & 1]);
+            if (s_off + s < tail_sub) {                      // wave-uniform
+                if (s + 2 < NSUB && s_off + s + 2 < tail_sub) load_frags(raw[s & 1], scur, s + 2);
+                if (s + 1 < NSUB && s_off + s + 1 < tail_sub) unpack(raw[(s + 1) & 1], unp[(s + 1) & 1]);
                 mfma_all(unp[s & 1]);
             }
         }
@@ -342,111 +353,153 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     wait_vm<0>();
     lds_barrier();
 
-    // ---- epilogue.  Accumulator element e of block (i, j): output channel
-    // n0 + wn WN + 32 j + 8 (e / 4) + 4 fk + e % 4, token m0 + wm WM + 32 i + frow.
-    if constexpr (MODE == MODE_I32) {
+    // ---- K split: wave kh finishes the token blocks i of half kh; it hands the other half's partial sums to
+    // its partner (same wave tile, other K half) through LDS and adds the partner's to its own.
+    if constexpr (KS == 2) {
+        constexpr int HF = FM / 2;
+        int* give = reinterpret_cast<int*>(smem + (size_t)wave * XCH);
+        const int* take = reinterpret_cast<const int*>(smem + (size_t)(wave ^ (WGM * WGN)) * XCH);
+        static_assert(((WGM * WGN) & (WGM * WGN - 1)) == 0, "the partner is the wave with the other kh bit");
+        auto hand_over = [&](auto khc) {
+            constexpr int OTHER = (1 - decltype(khc)::value) * HF;
 #pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            const int t = m0 + wm * WM + 32 * i + frow;
+            for (int ii = 0; ii < HF; ++ii)
 #pragma unroll
-            for (int j = 0; j < FN; ++j)
+                for (int j = 0; j < FN; ++j)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) {
-                    const int n = n0 + wn * WN + 32 * j + 8 * (e >> 2) + 4 * fk + (e & 3);
-                    if (t < T && n < N) static_cast<int32_t*>(out)[(int64_t)t * ldo + n] = acc[i][j][e] >> 8;
-                }
-        }
-    } else {
-        // all waves are past the last barrier of the K loop: the stages are free for staging
-        unsigned char* slab = smem + (size_t)wave * SLAB;
-        float* sc = reinterpret_cast<float*>(smem + (size_t)NW * SLAB);     // [BM] token scales, [BN] channel scales
-        int* zc = reinterpret_cast<int*>(sc + ROWS);                        // [BM] zero points, [BN] weight row sums
+                    for (int e = 0; e < 16; ++e) give[((ii * FN + j) * 16 + e) * 64 + lane] = acc[OTHER + ii][j][e];
+        };
+        auto add_partner = [&](auto khc) {
+            constexpr int MINE = decltype(khc)::value * HF;
 #pragma unroll
-        for (int q = 0; q < PRE; ++q) {
-            const int idx = tid + NT * q;
-            if (idx < ROWS) {
-                sc[idx] = pre[q];
-                if constexpr (MODE == MODE_ASYM) zc[idx] = prez[q];
-            }
-        }
+            for (int ii = 0; ii < HF; ++ii)
+#pragma unroll
+                for (int j = 0; j < FN; ++j)
+#pragma unroll
+                    for (int e = 0; e < 16; ++e) acc[MINE + ii][j][e] += take[((ii * FN + j) * 16 + e) * 64 + lane];
+        };
+        if (kh == 0) hand_over(std::integral_constant<int, 0>{});
+        else hand_over(std::integral_constant<int, 1>{});
         lds_barrier();
-        f32x4 swv[FN][4];
-        int wsv[FN][4][4];
-#pragma unroll
-        for (int j = 0; j < FN; ++j)
-#pragma unroll
-            for (int eg = 0; eg < 4; ++eg) {
-                swv[j][eg] = *reinterpret_cast<const f32x4*>(sc + BM + wn * WN + 32 * j + 8 * eg + 4 * fk);
-                if (MODE == MODE_ASYM) {
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) wsv[j][eg][q] = zc[BM + wn * WN + 32 * j + 8 * eg + 4 * fk + q];
-                }
-            }
-        uint16_t* y = static_cast<uint16_t*>(out);
-#pragma unroll
-        for (int i = 0; i < FM; ++i) {
-            const int t = min(m0 + wm * WM + 32 * i + frow, T - 1);
-            const float sxs = sc[wm * WM + 32 * i + frow];
-            int zoff = 0;
-            if (MODE == MODE_ASYM) zoff = (zc[wm * WM + 32 * i + frow] - 8) * 256;
-#pragma unroll
-            for (int j = 0; j < FN; ++j)
-#pragma unroll
-                for (int eg = 0; eg < 4; ++eg) {
-                    float f[4];
-#pragma unroll
-                    for (int q = 0; q < 4; ++q) {
-                        int a = acc[i][j][4 * eg + q];
-                        if (MODE == MODE_ASYM) a -= zoff * wsv[j][eg][q];
-                        f[q] = (float)a * sxs * swv[j][eg][q];
-                    }
-                    const u32x2 pk = u32x2{pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3])};
-                    *reinterpret_cast<u32x2*>(slab + frow * (WN * 2) + (32 * j + 8 * eg + 4 * fk) * 2) = pk;
-                }
-            // the slab is private to the wave: no workgroup barrier, only this wave's LDS traffic
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-            const int tbase = m0 + wm * WM + 32 * i, nbase = n0 + wn * WN;
-            if (vec_store) {
-                constexpr int CPS = WN / 8;                   // 16-byte chunks per slab row
-#pragma unroll
-                for (int c = lane; c < 32 * CPS; c += 64) {
-                    const int row = c / CPS, col = (c % CPS) * 8;
-                    const u32x4 v = *reinterpret_cast<const u32x4*>(slab + row * (WN * 2) + col * 2);
-                    if (tbase + row < T && nbase + col < N)
-                        *reinterpret_cast<u32x4*>(y + (int64_t)(tbase + row) * ldo + nbase + col) = v;
-                }
-            } else {
-                for (int c = lane; c < 32 * WN; c += 64) {
-                    const int row = c / WN, col = c % WN;
-                    if (tbase + row < T && nbase + col < N)
-                        y[(int64_t)(tbase + row) * ldo + nbase + col] =
-                            *reinterpret_cast<const uint16_t*>(slab + row * (WN * 2) + col * 2);
-                }
-            }
-            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-        }
+        if (kh == 0) add_partner(std::integral_constant<int, 0>{});
+        else add_partner(std::integral_constant<int, 1>{});
+        lds_barrier();                                      // the stages are reused below
     }
+
+    // The token blocks i this wave finishes: all FM of its tile, or with a K split the half kh.
+    constexpr int IH = FM / KS;
+    auto epilogue = [&](auto khc) {
+        constexpr int I0 = decltype(khc)::value * IH;
+        // ---- epilogue.  Accumulator element e of block (i, j): output channel
+        // n0 + wn WN + 32 j + 8 (e / 4) + 4 fk + e % 4, token m0 + wm WM + 32 i + frow.
+        if constexpr (MODE == MODE_I32) {
+    #pragma unroll
+            for (int ii = 0; ii < IH; ++ii) {
+                const int i = I0 + ii;
+                const int t = m0 + wm * WM + 32 * i + frow;
+    #pragma unroll
+                for (int j = 0; j < FN; ++j)
+    #pragma unroll
+                    for (int e = 0; e < 16; ++e) {
+                        const int n = n0 + wn * WN + 32 * j + 8 * (e >> 2) + 4 * fk + (e & 3);
+                        if (t < T && n < N) static_cast<int32_t*>(out)[(int64_t)t * ldo + n] = acc[i][j][e] >> 8;
+                    }
+            }
+        } else {
+            // all waves are past the last barrier of the K loop: the stages are free for staging
+            unsigned char* slab = smem + (size_t)wave * SLAB;
+            float* sc = reinterpret_cast<float*>(smem + (size_t)NW * SLAB);     // [BM] token scales, [BN] channel scales
+            int* zc = reinterpret_cast<int*>(sc + ROWS);                        // [BM] zero points, [BN] weight row sums
+    #pragma unroll
+            for (int q = 0; q < PRE; ++q) {
+                const int idx = tid + NT * q;
+                if (idx < ROWS) {
+                    sc[idx] = pre[q];
+                    if constexpr (MODE == MODE_ASYM) zc[idx] = prez[q];
+                }
+            }
+            lds_barrier();
+            f32x4 swv[FN][4];
+            int wsv[FN][4][4];
+    #pragma unroll
+            for (int j = 0; j < FN; ++j)
+    #pragma unroll
+                for (int eg = 0; eg < 4; ++eg) {
+                    swv[j][eg] = *reinterpret_cast<const f32x4*>(sc + BM + wn * WN + 32 * j + 8 * eg + 4 * fk);
+                    if (MODE == MODE_ASYM) {
+    #pragma unroll
+                        for (int q = 0; q < 4; ++q) wsv[j][eg][q] = zc[BM + wn * WN + 32 * j + 8 * eg + 4 * fk + q];
+                    }
+                }
+            uint16_t* y = static_cast<uint16_t*>(out);
+    #pragma unroll
+            for (int ii = 0; ii < IH; ++ii) {
+                const int i = I0 + ii;
+                const int t = min(m0 + wm * WM + 32 * i + frow, T - 1);
+                const float sxs = sc[wm * WM + 32 * i + frow];
+                int zoff = 0;
+                if (MODE == MODE_ASYM) zoff = (zc[wm * WM + 32 * i + frow] - 8) * 256;
+    #pragma unroll
+                for (int j = 0; j < FN; ++j)
+    #pragma unroll
+                    for (int eg = 0; eg < 4; ++eg) {
+                        float f[4];
+    #pragma unroll
+                        for (int q = 0; q < 4; ++q) {
+                            int a = acc[i][j][4 * eg + q];
+                            if (MODE == MODE_ASYM) a -= zoff * wsv[j][eg][q];
+                            f[q] = (float)a * sxs * swv[j][eg][q];
+                        }
+                        const u32x2 pk = u32x2{pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3])};
+                        *reinterpret_cast<u32x2*>(slab + frow * (WN * 2) + (32 * j + 8 * eg + 4 * fk) * 2) = pk;
+                    }
+                // the slab is private to the wave: no workgroup barrier, only this wave's LDS traffic
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                const int tbase = m0 + wm * WM + 32 * i, nbase = n0 + wn * WN;
+                if (vec_store) {
+                    constexpr int CPS = WN / 8;                   // 16-byte chunks per slab row
+    #pragma unroll
+                    for (int c = lane; c < 32 * CPS; c += 64) {
+                        const int row = c / CPS, col = (c % CPS) * 8;
+                        const u32x4 v = *reinterpret_cast<const u32x4*>(slab + row * (WN * 2) + col * 2);
+                        if (tbase + row < T && nbase + col < N)
+                            *reinterpret_cast<u32x4*>(y + (int64_t)(tbase + row) * ldo + nbase + col) = v;
+                    }
+                } else {
+                    for (int c = lane; c < 32 * WN; c += 64) {
+                        const int row = c / WN, col = c % WN;
+                        if (tbase + row < T && nbase + col < N)
+                            y[(int64_t)(tbase + row) * ldo + nbase + col] =
+                                *reinterpret_cast<const uint16_t*>(slab + row * (WN * 2) + col * 2);
+                    }
+                }
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+            }
+        }
+    };
+    if (KS == 1 || kh == 0) epilogue(std::integral_constant<int, 0>{});
+    else epilogue(std::integral_constant<int, KS - 1>{});
 }
 
-template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE>
+template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE, int KS = 1>
 pme_status launch_tile(const GemmArgs& a) {
     const int kb = (int)(a.d_e / 2);
     if (kb % 64) return PME_ERR_UNSUPPORTED_PATH;      // whole sub-steps; the last K step may be half as long
     if ((int64_t)std::max(a.T, a.N) * kb >= (int64_t(1) << 32)) return PME_ERR_UNSUPPORTED_PATH;   // 32-bit DMA offsets
     const int tiles_m = (int)((a.T + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WGM * WGN);
+    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WGM * WGN * KS);
     const size_t lds = (size_t)NSTAGE * (BM + BN) * RB;
     if (lds > 64 * 1024) {
         static std::atomic<uint32_t> done[3];
-        if (allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_BF16>, (int)lds, done[0]) != PME_OK ||
-            allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_ASYM>, (int)lds, done[1]) != PME_OK ||
-            allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_I32>, (int)lds, done[2]) != PME_OK)
+        if (allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_BF16, KS>, (int)lds, done[0]) != PME_OK ||
+            allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_ASYM, KS>, (int)lds, done[1]) != PME_OK ||
+            allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_I32, KS>, (int)lds, done[2]) != PME_OK)
             return PME_ERR_HIP;
     }
     // 16-byte output pieces need 8-element alignment of N, the pitch and the base
     const int vec = (a.N % 8 == 0 && a.ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0) ? 1 : 0;
 #define PME_LAUNCH(MODE)                                                                                        \
-    hipLaunchKernelGGL((k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE>), grid, block, lds, a.stream, a.qx, a.qw, \
+    hipLaunchKernelGGL((k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE, KS>), grid, block, lds, a.stream, a.qx, a.qw, \
                        a.sx, a.sw, a.zx, a.wsum, (int)a.T, (int)a.N, kb, a.y, a.ldy, tiles_m, tiles_n, xcd_grid_m(tiles_m, tiles_n, BM, BN), vec)
     if (a.out_i32) PME_LAUNCH(MODE_I32);
     else if (a.zx) PME_LAUNCH(MODE_ASYM);
@@ -475,10 +528,12 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
         // (a half-length last step is supported but measured no faster than 64-byte steps, so those are kept
         // when d_e is not a multiple of 256)
         const bool wide = (a.d_e % 256) == 0;
+        // (with 64-byte steps 128 x 192 on 4 waves beats 128 x 256 on 8 by a quarter; where the output only
+        // gives a compute unit 128 x 128, splitting K between wave pairs gains 3-10 % over 64 x 64 wave tiles)
         if (tiles(256, 256) >= cus) id = wide ? 11 : 8;
-        else if (tiles(128, 256) >= cus) id = wide ? 16 : 2;
+        else if (wide && tiles(128, 256) >= cus) id = 16;
         else if (tiles(128, 192) >= cus) id = wide ? 15 : 9;
-        else if (tiles(128, 128) >= cus) id = wide ? 13 : 4;
+        else if (tiles(128, 128) >= cus) id = wide ? 19 : 4;
         else if (tiles(64, 128) >= cus / 2) id = 6;
         else id = 7;
     }
@@ -502,6 +557,9 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
         case 16: return launch_tile<128, 256, 2, 4, 128, 3>(a);    // 8 waves of 64 x 64
         case 17: return launch_tile<256, 128, 4, 2, 128, 3>(a);    // 8 waves of 64 x 64
         case 18: return launch_tile<256, 128, 2, 2, 128, 3>(a);    // 4 waves of 128 x 64
+        // two waves per wave tile, each taking half of every K step
+        case 19: return launch_tile<128, 128, 1, 2, 128, 3, 2>(a); // 2 x 2 waves of 128 x 64
+        case 20: return launch_tile<128, 192, 1, 2, 128, 3, 2>(a); // 2 x 2 waves of 128 x 96
     }
     return PME_ERR_UNSUPPORTED_PATH;
 }

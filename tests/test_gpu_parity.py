@@ -180,7 +180,7 @@ def test_gemm_accumulators_and_epilogue(name, T, N, d_e, paths):
 
 
 @pytest.mark.parametrize("d_e", (1280, 1152, 128))
-@pytest.mark.parametrize("tile", range(1, 19))
+@pytest.mark.parametrize("tile", range(1, 21))
 def test_gemm_every_tile_configuration(tile, d_e):
     # every entry of the MFMA kernel's tile table, forced through the tuning hook: ragged T and N; K of
     # 5 whole steps of 128 bytes, of 4.5 (a half-length last step), and of a single half step; extreme rows
