@@ -333,9 +333,11 @@ pme_status launch_mxgemm_mfma(const MxGemmArgs& a) {
     int id = g_mx_tile_override;
     if (id == 0) {
         const bool wide = (a.d_e % 256) == 0;
+        // from a sweep of every tile over 9 shapes
         if (tiles(256, 256) >= cus) id = wide ? 8 : 2;
-        else if (tiles(128, 192) >= cus && tiles(128, 256) < cus) id = wide ? 6 : 5;
-        else if (tiles(128, 128) >= cus) id = wide ? 3 : 4;
+        else if (wide && tiles(256, 128) >= cus) id = 9;
+        else if (tiles(128, 192) >= cus && (!wide || tiles(128, 256) < cus)) id = wide ? 6 : 5;
+        else if (tiles(128, 128) >= cus / 2) id = wide ? 3 : 4;
         else id = 7;
     }
     switch (id) {
