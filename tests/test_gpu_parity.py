@@ -232,6 +232,30 @@ def test_gemm_tile_map_is_a_bijection(tm, tn):
         assert np.array_equal(acc, acc_ref), f"tile {tile}: {np.count_nonzero(acc != acc_ref)} accumulators differ"
 
 
+@pytest.mark.parametrize("tile", (9, 11, 13, 19, 20))
+def test_gemm_asymmetric_on_the_default_tiles(tile):
+    # the asymmetric epilogue (zero points, weight row sums) on the tiles the automatic choice uses,
+    # K split included; 4.5 K steps of 128 bytes, ragged T and N
+    rng = np.random.default_rng(tile)
+    T, N, d_e = 300, 520, 1152
+    q = rng.integers(0, 16, size=(T, d_e), dtype=np.uint8)
+    z = rng.integers(0, 16, size=T).astype(np.int32)
+    qw = rng.integers(-8, 8, size=(N, d_e), dtype=np.int8)
+    sx = rng.uniform(0.01, 2.0, T).astype(np.float32)
+    sw = rng.uniform(0.001, 0.01, N).astype(np.float32)
+    y_ref = oracle.dequant_asym_bf16(oracle.int_gemm(q, qw), sx, z, qw, sw)
+    wd = torch.from_numpy(oracle.pack_int4(qw)).cuda()
+    wsum = pme.weight_rowsum(wd)
+    pme.set_path(MFMA)
+    pme.set_gemm_tile(tile)
+    try:
+        y = pme.w4a4_gemm_asym(torch.from_numpy(oracle.pack_int4(q)).cuda(), torch.from_numpy(sx).cuda(),
+                               torch.from_numpy(z).cuda(), wd, torch.from_numpy(sw).cuda(), wsum)
+    finally:
+        pme.set_gemm_tile(0)
+    check_bf16(y.to(torch.float32).cpu().numpy(), y_ref)
+
+
 @pytest.mark.parametrize("T", (150, 8))
 @pytest.mark.parametrize("path", (GENERIC, MFMA))
 def test_gemm_asymmetric(path, T):
