@@ -346,7 +346,12 @@ def main() -> int:
         t_g = _event_ms(lambda: pme.mxfp4_gemm(qx4, ex4, qw4, ew4, b["y"]), it)
         out["mxfp4"] = {"layer_us": t_l * 1e3, "layer_tflops": ops / (t_l * 1e-3) / 1e12, "rotate_quant_us": t_r * 1e3,
                         "gemm_us": t_g * 1e3, "gemm_tflops": ops / (t_g * 1e-3) / 1e12, "gemm_peak_tflops": 10100.0,
-                        "gemm_frac": ops / (t_g * 1e-3) / 1e12 / 10100.0}
+                        "gemm_frac": ops / (t_g * 1e-3) / 1e12 / 10100.0, "gemm_traffic": None}
+        if os.path.exists(traffic_file):
+            with open(traffic_file) as f:
+                tr4 = json.load(f).get(sp.name + "_mxfp4", {}).get("w4a4_gemm")
+            if tr4:
+                out["mxfp4"]["gemm_traffic"] = tr4["total_bytes"]
     if probes:
         out["rotate_quant"]["measured_peak"] = probes["probe_copy"]["gbs"]
         out["rotate_quant"]["frac_of_measured"] = rot_gbs / probes["probe_copy"]["gbs"]
