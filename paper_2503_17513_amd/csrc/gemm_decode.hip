@@ -1,4 +1,4 @@
-// W4A4 GEMM for decode shapes (at most 16 tokens): memory-bound on the packed weights.
+// W4A4 GEMM for decode shapes (at most 64 tokens, in groups of 16): memory-bound on the packed weights.
 //
 //   acc[t][n] = sum_j qx[t][j] qw[n][j],  y[t][n] = bf16(acc * sx[t] * sw[n])   (paper Sections 3 and 4).
 //
@@ -21,7 +21,9 @@ typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 enum { MODE_BF16 = 0, MODE_ASYM = 1, MODE_I32 = 2 };
 constexpr int kBatch = 6;      // chunks a wave keeps in flight at once
 
-template <int NW, int MODE>
+// TG: groups of 16 tokens (T <= 16 TG).  The weight chunks a wave has loaded and unpacked meet the token chunks
+// of every group, so the weights are still read exactly once.
+template <int NW, int MODE, int TG>
 __global__ void __launch_bounds__(64 * NW)
 k_gemm_decode(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
               const float* __restrict__ sx, const float* __restrict__ sw,
@@ -34,64 +36,82 @@ k_gemm_decode(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     const int nchunks = kb >> 6;
     const int c0 = (int)(((int64_t)wave * nchunks) / NW), c1 = (int)(((int64_t)(wave + 1) * nchunks) / NW);
     const uint8_t* wrow = qw + (int64_t)min(n0 + r, N - 1) * kb + kg * 16;
-    const uint8_t* xrow = qx + (int64_t)min(r, T - 1) * kb + kg * 16;
-
-    i32x4 acc = {0, 0, 0, 0};
-    for (int c = c0; c < c1; c += kBatch) {
-        u32x4 w[kBatch], x[kBatch];
+    const uint8_t* xrow[TG];
 #pragma unroll
-        for (int i = 0; i < kBatch; ++i) {
+    for (int g = 0; g < TG; ++g) xrow[g] = qx + (int64_t)min(16 * g + r, T - 1) * kb + kg * 16;
+    constexpr int kB = TG > 2 ? 4 : kBatch;            // chunks in flight: bounded by registers with many groups
+
+    i32x4 acc[TG];
+#pragma unroll
+    for (int g = 0; g < TG; ++g) acc[g] = i32x4{0, 0, 0, 0};
+    for (int c = c0; c < c1; c += kB) {
+        u32x4 w[kB], x[TG][kB];
+#pragma unroll
+        for (int i = 0; i < kB; ++i) {
             const int cc = min(c + i, c1 - 1);          // surplus slots repeat the last chunk and are not used
             w[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow + (int64_t)cc * 64));
-            x[i] = *reinterpret_cast<const u32x4*>(xrow + (int64_t)cc * 64);
+#pragma unroll
+            for (int g = 0; g < TG; ++g) x[g][i] = *reinterpret_cast<const u32x4*>(xrow[g] + (int64_t)cc * 64);
         }
 #pragma unroll
-        for (int i = 0; i < kBatch; ++i) {
+        for (int i = 0; i < kB; ++i) {
             if (c + i < c1) {
-                u32x4 xv = x[i];
-                if (MODE == MODE_ASYM) xv ^= 0x88888888u;      // unsigned code u: u ^ 8 as a signed nibble is u - 8
-                i32x4 wlo, whi, xlo, xhi;
+                i32x4 wlo, whi;
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     wlo[e] = (int)((w[i][e] & 0x0F0F0F0Fu) << 4);
                     whi[e] = (int)(w[i][e] & 0xF0F0F0F0u);
-                    xlo[e] = (int)((xv[e] & 0x0F0F0F0Fu) << 4);
-                    xhi[e] = (int)(xv[e] & 0xF0F0F0F0u);
                 }
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(wlo, xlo, acc, 0, 0, 0);
-                acc = __builtin_amdgcn_mfma_i32_16x16x64_i8(whi, xhi, acc, 0, 0, 0);
+#pragma unroll
+                for (int g = 0; g < TG; ++g) {
+                    u32x4 xv = x[g][i];
+                    if (MODE == MODE_ASYM) xv ^= 0x88888888u;      // unsigned code u: u ^ 8 as a signed nibble is u - 8
+                    i32x4 xlo, xhi;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        xlo[e] = (int)((xv[e] & 0x0F0F0F0Fu) << 4);
+                        xhi[e] = (int)(xv[e] & 0xF0F0F0F0u);
+                    }
+                    acc[g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(wlo, xlo, acc[g], 0, 0, 0);
+                    acc[g] = __builtin_amdgcn_mfma_i32_16x16x64_i8(whi, xhi, acc[g], 0, 0, 0);
+                }
             }
         }
     }
+    // one group at a time through the reduction buffer
 #pragma unroll
-    for (int i = 0; i < 4; ++i) part[wave][lane][i] = acc[i];
-    __syncthreads();
-    if (tid < 256) {
-        // element tid = 4 * lane' + i of the 16 x 16 tile: channel 4 * (lane' / 16) + i, token lane' % 16
-        const int ln = tid >> 2, i = tid & 3;
-        int s = 0;
+    for (int g = 0; g < TG; ++g) {
+        if (g > 0) __syncthreads();                     // the previous group has been read
 #pragma unroll
-        for (int w = 0; w < NW; ++w) s += part[w][ln][i];
-        s >>= 8;                                        // exact: the low 8 bits are zero
-        const int t = ln & 15, n = n0 + 4 * (ln >> 4) + i;
-        if (t < T && n < N) {
-            if (MODE == MODE_ASYM) s -= (zx[t] - 8) * wsum[n];
-            if (MODE == MODE_I32) {
-                static_cast<int32_t*>(out)[(int64_t)t * ldo + n] = s;
-            } else {
-                const float y = (float)s * sx[t] * sw[n];
-                static_cast<uint16_t*>(out)[(int64_t)t * ldo + n] = f32_to_bf16_bits(y);
+        for (int i = 0; i < 4; ++i) part[wave][lane][i] = acc[g][i];
+        __syncthreads();
+        if (tid < 256) {
+            // element tid = 4 * lane' + i of the 16 x 16 tile: channel 4 * (lane' / 16) + i, token lane' % 16
+            const int ln = tid >> 2, i = tid & 3;
+            int s = 0;
+#pragma unroll
+            for (int w = 0; w < NW; ++w) s += part[w][ln][i];
+            s >>= 8;                                    // exact: the low 8 bits are zero
+            const int t = 16 * g + (ln & 15), n = n0 + 4 * (ln >> 4) + i;
+            if (t < T && n < N) {
+                if (MODE == MODE_ASYM) s -= (zx[t] - 8) * wsum[n];
+                if (MODE == MODE_I32) {
+                    static_cast<int32_t*>(out)[(int64_t)t * ldo + n] = s;
+                } else {
+                    const float y = (float)s * sx[t] * sw[n];
+                    static_cast<uint16_t*>(out)[(int64_t)t * ldo + n] = f32_to_bf16_bits(y);
+                }
             }
         }
     }
 }
 
-template <int NW>
+template <int NW, int TG>
 pme_status launch_nw(const GemmArgs& a) {
     const dim3 grid((unsigned)((a.N + 15) / 16)), block(64 * NW);
     const int kb = (int)(a.d_e / 2);
-#define PME_LAUNCH(MODE)                                                                                   \
-    hipLaunchKernelGGL((k_gemm_decode<NW, MODE>), grid, block, 0, a.stream, a.qx, a.qw, a.sx, a.sw, a.zx, a.wsum, \
+#define PME_LAUNCH(MODE)                                                                                       \
+    hipLaunchKernelGGL((k_gemm_decode<NW, MODE, TG>), grid, block, 0, a.stream, a.qx, a.qw, a.sx, a.sw, a.zx, a.wsum, \
                        (int)a.T, (int)a.N, kb, a.y, a.ldy)
     if (a.out_i32) PME_LAUNCH(MODE_I32);
     else if (a.zx) PME_LAUNCH(MODE_ASYM);
@@ -100,17 +120,25 @@ pme_status launch_nw(const GemmArgs& a) {
     return hip_status(hipGetLastError());
 }
 
+template <int TG>
+pme_status launch_groups(const GemmArgs& a) {
+    const int64_t nchunks = a.d_e / 128;
+    if (nchunks >= 32) return launch_nw<16, TG>(a);
+    if (nchunks >= 8) return launch_nw<8, TG>(a);
+    return launch_nw<4, TG>(a);
+}
+
 }  // namespace
 
 pme_status launch_gemm_decode(const GemmArgs& a) {
-    // at most 16 tokens, whole 64-byte chunks, 16-byte aligned rows
-    if (a.T > 16 || a.d_e % 128 || a.d_e > (1 << 17)) return PME_ERR_UNSUPPORTED_PATH;
+    // at most 64 tokens, whole 64-byte chunks, 16-byte aligned rows
+    if (a.T > 64 || a.d_e % 128 || a.d_e > (1 << 17)) return PME_ERR_UNSUPPORTED_PATH;
     if ((reinterpret_cast<uintptr_t>(a.qx) & 15) || (reinterpret_cast<uintptr_t>(a.qw) & 15)) return PME_ERR_UNSUPPORTED_PATH;
     if (a.zx && a.out_i32) return PME_ERR_UNSUPPORTED_PATH;
-    const int64_t nchunks = a.d_e / 128;
-    if (nchunks >= 32) return launch_nw<16>(a);
-    if (nchunks >= 8) return launch_nw<8>(a);
-    return launch_nw<4>(a);
+    if (a.T <= 16) return launch_groups<1>(a);
+    if (a.T <= 32) return launch_groups<2>(a);
+    if (a.T <= 48) return launch_groups<3>(a);
+    return launch_groups<4>(a);
 }
 
 }  // namespace pme

@@ -63,7 +63,10 @@ pme_status run_gemm(const pme::GemmArgs& a) {
     if (a.T == 0 || a.N == 0) return PME_OK;
     int path = g_path.load();
     if (path != PME_PATH_GENERIC) {
-        pme_status s = (a.T <= 16) ? pme::launch_gemm_decode(a) : pme::launch_gemm_mfma(a);
+        // few tokens: the weight-streaming kernel, unless the output is wide enough to fill the chip with tiles
+        const bool stream_weights = a.T <= 16 || (a.T <= 64 && a.N < 8192);       // 64 x 64 tiles: fewer than 128 of them
+        pme_status s = stream_weights ? pme::launch_gemm_decode(a) : pme::launch_gemm_mfma(a);
+        if (s == PME_ERR_UNSUPPORTED_PATH && stream_weights && a.T > 16) s = pme::launch_gemm_mfma(a);
         if (s != PME_ERR_UNSUPPORTED_PATH || path == PME_PATH_MFMA) return s;
     }
     return pme::launch_gemm_generic(a);

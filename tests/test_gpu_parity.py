@@ -151,7 +151,12 @@ GEMM_CASES = [
     ("decode_one_token_long_k", 1, 520, 15360, (GENERIC, MFMA)),
     ("decode_five_tokens_odd_chunks_ragged_n", 5, 36, 640, (GENERIC, MFMA)),
     ("decode_nine_tokens", 9, 50, 640, (GENERIC, MFMA)),
-    ("seventeen_tokens_use_the_tiled_kernel", 17, 64, 256, (GENERIC, MFMA)),
+    # 17 .. 64 tokens: the weight-streaming kernel with 2, 3 or 4 groups of 16 tokens
+    ("decode_17_tokens", 17, 64, 256, (GENERIC, MFMA)),
+    ("decode_33_tokens_odd_chunks_ragged_n", 33, 100, 640, (GENERIC, MFMA)),
+    ("decode_48_tokens", 48, 40, 384, (GENERIC, MFMA)),
+    ("decode_64_tokens_shape", 64, 2048, 8448, (GENERIC, MFMA)),
+    ("sixty_five_tokens_use_the_tiled_kernel", 65, 72, 256, (GENERIC, MFMA)),
 ]
 
 
@@ -256,7 +261,7 @@ def test_gemm_asymmetric_on_the_default_tiles(tile):
     check_bf16(y.to(torch.float32).cpu().numpy(), y_ref)
 
 
-@pytest.mark.parametrize("T", (150, 8))
+@pytest.mark.parametrize("T", (150, 8, 40))
 @pytest.mark.parametrize("path", (GENERIC, MFMA))
 def test_gemm_asymmetric(path, T):
     rng = np.random.default_rng(8)
