@@ -310,6 +310,99 @@ k_mxgemm_generic(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex,
 
 int g_mx_tile_override = 0;
 
+// ---- few tokens (at most 32): memory-bound on the packed weights, like the int4 decode kernel.  One workgroup
+// owns 16 output channels and all of K; its waves split K into runs of 64-byte chunks (128 codes = 4 MX blocks),
+// every weight byte is loaded once into registers.  A chunk of 16 channels is one 16-byte load per lane (lane =
+// channel % 16 + 16 * block of the chunk) plus that block's scale byte, and feeds
+// v_mfma_scale_f32_16x16x128_f8f6f4 against the token chunks of up to TG groups of 16 tokens.  The waves'
+// partial 16 x 16 tiles (fp32) are summed through LDS.
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+constexpr int kMxBatch = 4;      // chunks a wave keeps in flight at once
+
+template <int NW, int TG>
+__global__ void __launch_bounds__(64 * NW)
+k_mxgemm_decode(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, const uint8_t* __restrict__ qw,
+                const uint8_t* __restrict__ ew, int T, int N, int kb, int eb, uint16_t* __restrict__ y, int64_t ldo) {
+    __shared__ float part[NW][64][4];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int r = lane & 15, kg = lane >> 4;
+    const int n0 = blockIdx.x * 16;
+    const int nchunks = kb >> 6;
+    const int c0 = (int)(((int64_t)wave * nchunks) / NW), c1 = (int)(((int64_t)(wave + 1) * nchunks) / NW);
+    const int64_t wr = min(n0 + r, N - 1);
+    const uint8_t* wrow = qw + wr * kb + kg * 16;
+    const uint8_t* wsrow = ew + wr * eb + kg;
+    const uint8_t* xrow[TG];
+    const uint8_t* xsrow[TG];
+#pragma unroll
+    for (int g = 0; g < TG; ++g) {
+        const int64_t xr = min(16 * g + r, T - 1);
+        xrow[g] = qx + xr * kb + kg * 16;
+        xsrow[g] = ex + xr * eb + kg;
+    }
+    f32x4 acc[TG];
+#pragma unroll
+    for (int g = 0; g < TG; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int c = c0; c < c1; c += kMxBatch) {
+        u32x4 w[kMxBatch], x[TG][kMxBatch];
+        uint32_t ws[kMxBatch], xs[TG][kMxBatch];
+#pragma unroll
+        for (int i = 0; i < kMxBatch; ++i) {
+            const int cc = min(c + i, c1 - 1);          // surplus slots repeat the last chunk and are not used
+            w[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow + (int64_t)cc * 64));
+            ws[i] = wsrow[cc * 4];
+#pragma unroll
+            for (int g = 0; g < TG; ++g) {
+                x[g][i] = *reinterpret_cast<const u32x4*>(xrow[g] + (int64_t)cc * 64);
+                xs[g][i] = xsrow[g][cc * 4];
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < kMxBatch; ++i) {
+            if (c + i < c1) {
+                const i32x8 wb = {(int)w[i][0], (int)w[i][1], (int)w[i][2], (int)w[i][3], 0, 0, 0, 0};
+#pragma unroll
+                for (int g = 0; g < TG; ++g) {
+                    const i32x8 xa = {(int)x[g][i][0], (int)x[g][i][1], (int)x[g][i][2], (int)x[g][i][3], 0, 0, 0, 0};
+                    acc[g] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(wb, xa, acc[g], 4, 4, 0, (int)ws[i], 0,
+                                                                               (int)xs[g][i]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int g = 0; g < TG; ++g) {
+        if (g > 0) __syncthreads();                     // the previous group has been read
+#pragma unroll
+        for (int i = 0; i < 4; ++i) part[wave][lane][i] = acc[g][i];
+        __syncthreads();
+        if (tid < 256) {
+            // element tid = 4 * lane' + i of the 16 x 16 tile: channel 4 * (lane' / 16) + i, token lane' % 16
+            const int ln = tid >> 2, i = tid & 3;
+            float sum = 0.f;
+#pragma unroll
+            for (int w2 = 0; w2 < NW; ++w2) sum += part[w2][ln][i];
+            const int t = 16 * g + (ln & 15), n = n0 + 4 * (ln >> 4) + i;
+            if (t < T && n < N) y[(int64_t)t * ldo + n] = f32_to_bf16_bits(sum);
+        }
+    }
+}
+
+template <int NW, int TG>
+pme_status launch_mx_decode_nw(const MxGemmArgs& a) {
+    hipLaunchKernelGGL((k_mxgemm_decode<NW, TG>), dim3((unsigned)((a.N + 15) / 16)), dim3(64 * NW), 0, a.stream, a.qx,
+                       a.ex, a.qw, a.ew, (int)a.T, (int)a.N, (int)(a.d_e / 2), (int)(a.d_e / 32),
+                       static_cast<uint16_t*>(a.y), a.ldy);
+    return hip_status(hipGetLastError());
+}
+template <int TG>
+pme_status launch_mx_decode_groups(const MxGemmArgs& a) {
+    const int64_t nchunks = a.d_e / 128;
+    if (nchunks >= 32) return launch_mx_decode_nw<16, TG>(a);
+    if (nchunks >= 8) return launch_mx_decode_nw<8, TG>(a);
+    return launch_mx_decode_nw<4, TG>(a);
+}
+
 }  // namespace
 
 void set_mxgemm_tile_override(int id) { g_mx_tile_override = id; }
@@ -320,6 +413,14 @@ pme_status launch_mxgemm_generic(const MxGemmArgs& a) {
     hipLaunchKernelGGL(k_mxgemm_generic, grid, dim3(256), 0, a.stream, a.qx, a.ex, a.qw, a.ew, (int)a.T, (int)a.N,
                        (int)a.d_e, static_cast<uint16_t*>(a.y), a.ldy);
     return hip_status(hipGetLastError());
+}
+
+pme_status launch_mxgemm_decode(const MxGemmArgs& a) {
+    // at most 32 tokens (beyond that the tiled kernel measured faster), whole 64-byte chunks, 16-byte aligned code rows
+    if (a.T > 32 || a.d_e % 128 || a.d_e > (1 << 20)) return PME_ERR_UNSUPPORTED_PATH;
+    if ((reinterpret_cast<uintptr_t>(a.qx) & 15) || (reinterpret_cast<uintptr_t>(a.qw) & 15)) return PME_ERR_UNSUPPORTED_PATH;
+    if (a.T <= 16) return launch_mx_decode_groups<1>(a);
+    return launch_mx_decode_groups<2>(a);
 }
 
 pme_status launch_mxgemm_mfma(const MxGemmArgs& a) {

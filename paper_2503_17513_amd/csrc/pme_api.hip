@@ -234,7 +234,10 @@ static pme_status run_mxgemm(const pme::MxGemmArgs& a) {
     if (a.T == 0 || a.N == 0) return PME_OK;
     int path = g_path.load();
     if (path != PME_PATH_GENERIC) {
-        pme_status s = pme::launch_mxgemm_mfma(a);
+        // few tokens: the weight-streaming kernel, unless the output is wide enough to fill the chip with tiles
+        const bool stream_weights = a.T <= 16 || (a.T <= 32 && a.N < 8192);
+        pme_status s = stream_weights ? pme::launch_mxgemm_decode(a) : pme::launch_mxgemm_mfma(a);
+        if (s == PME_ERR_UNSUPPORTED_PATH && stream_weights) s = pme::launch_mxgemm_mfma(a);
         if (s != PME_ERR_UNSUPPORTED_PATH || path == PME_PATH_MFMA) return s;
     }
     return pme::launch_mxgemm_generic(a);

@@ -36,6 +36,7 @@ struct MxGemmArgs {
 };
 pme_status launch_mxgemm_generic(const MxGemmArgs& a);
 pme_status launch_mxgemm_mfma(const MxGemmArgs& a);
+pme_status launch_mxgemm_decode(const MxGemmArgs& a);
 
 struct GemmArgs {
     const uint8_t* qx;

@@ -103,7 +103,12 @@ def check_mx_gemm(y_gpu, qx, ex, qw, ew):
 
 GEMM_CASES = [("small_ragged", 50, 70, 96, (GENERIC,)), ("one_k_step", 40, 72, 128, (GENERIC, MFMA)),
               ("ragged_tiles", 300, 200, 2176, (GENERIC, MFMA)), ("wide_rows", 260, 520, 1280, (GENERIC, MFMA)),
-              ("c2_shape_rows", 2048, 384, 2176, (MFMA,)), ("big_tile", 1024, 4096, 512, (MFMA,))]
+              ("c2_shape_rows", 2048, 384, 2176, (MFMA,)), ("big_tile", 1024, 4096, 512, (MFMA,)),
+              # at most 32 tokens: the weight-streaming kernel, 1 or 2 groups of 16 tokens; beyond: tiles
+              ("decode_shape", 8, 2048, 8448, (GENERIC, MFMA)), ("decode_one_token_one_chunk", 1, 24, 128, (GENERIC, MFMA)),
+              ("decode_16_ragged_n", 16, 100, 384, (GENERIC, MFMA)), ("decode_33_odd_chunks", 33, 40, 640, (GENERIC, MFMA)),
+              ("decode_48", 48, 72, 1280, (MFMA,)), ("decode_64", 64, 130, 2176, (GENERIC, MFMA)),
+              ("sixty_five_tokens_tiled", 65, 72, 256, (MFMA,))]
 
 
 @pytest.mark.parametrize("name,T,N,d_e,paths", GEMM_CASES, ids=[c[0] for c in GEMM_CASES])
