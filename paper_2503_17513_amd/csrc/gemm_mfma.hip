@@ -4,12 +4,13 @@
 //   y[t][n]   = bf16(acc * sx[t] * sw[n]) (Section 4: per-token and per-channel scales).
 //
 // Both operands are K-contiguous packed int4.  A workgroup owns a BM x BN output tile and walks K
-// in steps of 128 codes (64 packed bytes per row).
-//  * HBM -> LDS: global_load_lds_dwordx4 (no registers, no VALU), three LDS stages, two K steps in
-//    flight while one is consumed.  The DMA instructions and the waits on them are issued from
+// in steps of 128 or 256 codes (64 or 128 packed bytes per row).
+//  * HBM -> LDS: global_load_lds_dwordx4 (no registers; scalar base + per-lane offset, so no VALU
+//    either), two or three LDS stages.  The DMA instructions and the waits on them are issued from
 //    inline assembly, so that the compiler does not order LDS reads of one stage after DMA writes
 //    to another; the per-step barrier waits for LDS traffic only and for all but the newest
-//    stage's DMA (vmcnt counts in order).
+//    stage's DMA (vmcnt counts in order).  The DMA instructions of a K step are spread between the
+//    matrix instructions of the region after the barrier (issuing one holds the wave up).
 //  * LDS -> registers: one ds_read_b128 per lane brings 32 codes, unpacked in registers into two
 //    int8 MFMA operands:   even codes (w & 0x0F0F0F0F) << 4,   odd codes w & 0xF0F0F0F0.
 //    A nibble moved to the top of a byte is 16 x its two's-complement value: no sign extension.
