@@ -19,11 +19,12 @@ typedef __attribute__((ext_vector_type(4))) int i32x4;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 
 enum { MODE_BF16 = 0, MODE_ASYM = 1, MODE_I32 = 2 };
-constexpr int kBatch = 6;      // chunks a wave keeps in flight at once
 
 // TG: groups of 16 tokens (T <= 16 TG).  The weight chunks a wave has loaded and unpacked meet the token chunks
 // of every group, so the weights are still read exactly once.
-template <int NW, int MODE, int TG>
+// kB: chunks a wave keeps in flight at once (its share of K is ceil(chunks / NW): one round of loads where
+// that fits in 8).
+template <int NW, int MODE, int TG, int kB>
 __global__ void __launch_bounds__(64 * NW)
 k_gemm_decode(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
               const float* __restrict__ sx, const float* __restrict__ sw,
@@ -39,7 +40,6 @@ k_gemm_decode(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     const uint8_t* xrow[TG];
 #pragma unroll
     for (int g = 0; g < TG; ++g) xrow[g] = qx + (int64_t)min(16 * g + r, T - 1) * kb + kg * 16;
-    constexpr int kB = TG > 2 ? 4 : kBatch;            // chunks in flight: bounded by registers with many groups
 
     i32x4 acc[TG];
 #pragma unroll
@@ -48,10 +48,11 @@ k_gemm_decode(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
         u32x4 w[kB], x[TG][kB];
 #pragma unroll
         for (int i = 0; i < kB; ++i) {
-            const int cc = min(c + i, c1 - 1);          // surplus slots repeat the last chunk and are not used
-            w[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow + (int64_t)cc * 64));
+            if (c + i < c1) {                           // wave-uniform: surplus slots load nothing
+                w[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow + (int64_t)(c + i) * 64));
 #pragma unroll
-            for (int g = 0; g < TG; ++g) x[g][i] = *reinterpret_cast<const u32x4*>(xrow[g] + (int64_t)cc * 64);
+                for (int g = 0; g < TG; ++g) x[g][i] = *reinterpret_cast<const u32x4*>(xrow[g] + (int64_t)(c + i) * 64);
+            }
         }
 #pragma unroll
         for (int i = 0; i < kB; ++i) {
@@ -106,18 +107,27 @@ k_gemm_decode(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     }
 }
 
-template <int NW, int TG>
-pme_status launch_nw(const GemmArgs& a) {
+template <int NW, int TG, int KB>
+pme_status launch_kb(const GemmArgs& a) {
     const dim3 grid((unsigned)((a.N + 15) / 16)), block(64 * NW);
     const int kb = (int)(a.d_e / 2);
 #define PME_LAUNCH(MODE)                                                                                       \
-    hipLaunchKernelGGL((k_gemm_decode<NW, MODE, TG>), grid, block, 0, a.stream, a.qx, a.qw, a.sx, a.sw, a.zx, a.wsum, \
+    hipLaunchKernelGGL((k_gemm_decode<NW, MODE, TG, KB>), grid, block, 0, a.stream, a.qx, a.qw, a.sx, a.sw, a.zx, a.wsum, \
                        (int)a.T, (int)a.N, kb, a.y, a.ldy)
     if (a.out_i32) PME_LAUNCH(MODE_I32);
     else if (a.zx) PME_LAUNCH(MODE_ASYM);
     else PME_LAUNCH(MODE_BF16);
 #undef PME_LAUNCH
     return hip_status(hipGetLastError());
+}
+
+template <int NW, int TG>
+pme_status launch_nw(const GemmArgs& a) {
+    // a wave's share of K in one round of loads where registers allow (8 chunks with up to two token groups)
+    const int64_t per_wave = (a.d_e / 128 + NW - 1) / NW;
+    if (TG > 2 || per_wave <= 4) return launch_kb<NW, TG, 4>(a);
+    if (per_wave <= 6) return launch_kb<NW, TG, 6>(a);
+    return launch_kb<NW, TG, (TG > 2 ? 4 : 8)>(a);
 }
 
 template <int TG>
