@@ -125,9 +125,13 @@ template <int NW, int TG>
 pme_status launch_nw(const GemmArgs& a) {
     // a wave's share of K in one round of loads where registers allow (8 chunks with up to two token groups)
     const int64_t per_wave = (a.d_e / 128 + NW - 1) / NW;
-    if (TG > 2 || per_wave <= 4) return launch_kb<NW, TG, 4>(a);
-    if (per_wave <= 6) return launch_kb<NW, TG, 6>(a);
-    return launch_kb<NW, TG, (TG > 2 ? 4 : 8)>(a);
+    if constexpr (TG > 2) {
+        return launch_kb<NW, TG, 4>(a);
+    } else {
+        if (per_wave <= 4) return launch_kb<NW, TG, 4>(a);
+        if (per_wave <= 6) return launch_kb<NW, TG, 6>(a);
+        return launch_kb<NW, TG, 8>(a);
+    }
 }
 
 template <int TG>

@@ -317,9 +317,9 @@ int g_mx_tile_override = 0;
 // v_mfma_scale_f32_16x16x128_f8f6f4 against the token chunks of up to TG groups of 16 tokens.  The waves'
 // partial 16 x 16 tiles (fp32) are summed through LDS.
 typedef __attribute__((ext_vector_type(4))) float f32x4;
-constexpr int kMxBatch = 4;      // chunks a wave keeps in flight at once
 
-template <int NW, int TG>
+// KB: chunks a wave keeps in flight at once (its share of K in one round of loads where that fits in 8).
+template <int NW, int TG, int KB>
 __global__ void __launch_bounds__(64 * NW)
 k_mxgemm_decode(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, const uint8_t* __restrict__ qw,
                 const uint8_t* __restrict__ ew, int T, int N, int kb, int eb, uint16_t* __restrict__ y, int64_t ldo) {
@@ -343,22 +343,24 @@ k_mxgemm_decode(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, 
     f32x4 acc[TG];
 #pragma unroll
     for (int g = 0; g < TG; ++g) acc[g] = f32x4{0.f, 0.f, 0.f, 0.f};
-    for (int c = c0; c < c1; c += kMxBatch) {
-        u32x4 w[kMxBatch], x[TG][kMxBatch];
-        uint32_t ws[kMxBatch], xs[TG][kMxBatch];
+    for (int c = c0; c < c1; c += KB) {
+        u32x4 w[KB], x[TG][KB];
+        uint32_t ws[KB], xs[TG][KB];
 #pragma unroll
-        for (int i = 0; i < kMxBatch; ++i) {
-            const int cc = min(c + i, c1 - 1);          // surplus slots repeat the last chunk and are not used
-            w[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow + (int64_t)cc * 64));
-            ws[i] = wsrow[cc * 4];
+        for (int i = 0; i < KB; ++i) {
+            if (c + i < c1) {                           // wave-uniform: surplus slots load nothing
+                const int cc = c + i;
+                w[i] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(wrow + (int64_t)cc * 64));
+                ws[i] = wsrow[cc * 4];
 #pragma unroll
-            for (int g = 0; g < TG; ++g) {
-                x[g][i] = *reinterpret_cast<const u32x4*>(xrow[g] + (int64_t)cc * 64);
-                xs[g][i] = xsrow[g][cc * 4];
+                for (int g = 0; g < TG; ++g) {
+                    x[g][i] = *reinterpret_cast<const u32x4*>(xrow[g] + (int64_t)cc * 64);
+                    xs[g][i] = xsrow[g][cc * 4];
+                }
             }
         }
 #pragma unroll
-        for (int i = 0; i < kMxBatch; ++i) {
+        for (int i = 0; i < KB; ++i) {
             if (c + i < c1) {
                 const i32x8 wb = {(int)w[i][0], (int)w[i][1], (int)w[i][2], (int)w[i][3], 0, 0, 0, 0};
 #pragma unroll
@@ -388,12 +390,24 @@ k_mxgemm_decode(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, 
     }
 }
 
-template <int NW, int TG>
-pme_status launch_mx_decode_nw(const MxGemmArgs& a) {
-    hipLaunchKernelGGL((k_mxgemm_decode<NW, TG>), dim3((unsigned)((a.N + 15) / 16)), dim3(64 * NW), 0, a.stream, a.qx,
+template <int NW, int TG, int KB>
+pme_status launch_mx_decode_kb(const MxGemmArgs& a) {
+    hipLaunchKernelGGL((k_mxgemm_decode<NW, TG, KB>), dim3((unsigned)((a.N + 15) / 16)), dim3(64 * NW), 0, a.stream, a.qx,
                        a.ex, a.qw, a.ew, (int)a.T, (int)a.N, (int)(a.d_e / 2), (int)(a.d_e / 32),
                        static_cast<uint16_t*>(a.y), a.ldy);
     return hip_status(hipGetLastError());
+}
+template <int NW, int TG>
+pme_status launch_mx_decode_nw(const MxGemmArgs& a) {
+    // (two token groups on 16 waves have 128 registers per lane: 4 chunks)
+    const int64_t per_wave = (a.d_e / 128 + NW - 1) / NW;
+    if constexpr (TG > 1 && NW == 16) {
+        return launch_mx_decode_kb<NW, TG, 4>(a);
+    } else {
+        if (per_wave <= 4) return launch_mx_decode_kb<NW, TG, 4>(a);
+        if (per_wave <= 6) return launch_mx_decode_kb<NW, TG, 6>(a);
+        return launch_mx_decode_kb<NW, TG, 8>(a);
+    }
 }
 template <int TG>
 pme_status launch_mx_decode_groups(const MxGemmArgs& a) {
