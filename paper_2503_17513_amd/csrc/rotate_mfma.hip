@@ -245,7 +245,9 @@ enum { OUT_SYM = 0, OUT_ASYM = 1, OUT_XHAT = 2, OUT_MXFP4 = 3 };   // int4 symme
 // fewer workgroups, which is what counts at small 2^k, where a token is only a few KB.
 // BGLOBAL: the P fragments are not staged in LDS but read from the table in device memory (L2) for every
 // token: for blocks whose fragments do not fit beside the token buffer (order 312: 140 KB of fragments).
-template <int KLOG2, int TPW, bool F32IN, int OUT, bool MULTI = false, bool BGLOBAL = false>
+// KSREG > 0 (with BGLOBAL): the workgroup reads its fragments (at most KSREG K steps) once, before the token
+// loop, and keeps them in registers.
+template <int KLOG2, int TPW, bool F32IN, int OUT, bool MULTI = false, bool BGLOBAL = false, int KSREG = 0>
 __global__ void __launch_bounds__((64 * max_waves<KLOG2, TPW>()))
 k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, int b, int ks_count, int slot,
               double gamma, uint8_t* __restrict__ qx, float* __restrict__ sx, int32_t* __restrict__ zx,
@@ -344,7 +346,15 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
         if (t < T) load_token_dma(t);       // in flight while the B fragments are fetched
     }
     // ---- once per workgroup: B fragments of P into LDS
-    if constexpr (BGLOBAL) {
+    static_assert(KSREG == 0 || BGLOBAL, "register-resident fragments come from the table in device memory");
+    u32x4 breg[TPW][KSREG > 0 ? KSREG : 1];
+    if constexpr (KSREG > 0) {
+#pragma unroll
+        for (int ti = 0; ti < TPW; ++ti)
+#pragma unroll
+            for (int ks = 0; ks < KSREG; ++ks)
+                breg[ti][ks] = g_ptable[slot][min(wave * TPW + ti, kMaxTiles - 1) * kMaxKs + min(ks, ks_count - 1)][lane];
+    } else if constexpr (BGLOBAL) {
         // nothing to stage
     } else if constexpr (MULTI) {
         for (int f = wave_hw; f < TPW * ks_count; f += nwaves_hw) {       // fragment f = ti ks_count + ks
@@ -382,15 +392,12 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
 
         // ---- base block on the matrix cores: Z^T[c][a'] = sum_a X~[a][c] P[a][a']
         f32x4 acc[TPW][MT];
-        auto base_block = [&](int ks, auto first) {     // first: the accumulators start from a literal zero
+        // first: the accumulators start from a literal zero; frag_of(ti): the B fragment of tile ti for this K step
+        auto base_block = [&](int ks, auto first, auto frag_of) {
             constexpr bool FIRST = decltype(first)::value;
             bf16x8 bfrag[TPW];
 #pragma unroll
-            for (int ti = 0; ti < TPW; ++ti)
-                if constexpr (BGLOBAL)
-                    bfrag[ti] = __builtin_bit_cast(bf16x8, g_ptable[slot][min(wave * TPW + ti, kMaxTiles - 1) * kMaxKs + ks][lane]);
-                else
-                    bfrag[ti] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(bsm + ((size_t)(ti * ks_count + ks) * 64 + lane) * 16));
+            for (int ti = 0; ti < TPW; ++ti) bfrag[ti] = frag_of(ti);
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 if constexpr (!F32IN) {
@@ -420,8 +427,25 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
                 }
             }
         };
-        base_block(0, std::true_type{});
-        for (int ks = 1; ks < ks_count; ++ks) base_block(ks, std::false_type{});
+        if constexpr (KSREG > 0) {
+            static_for<KSREG>([&](auto kc) {
+                constexpr int KS = decltype(kc)::value;
+                auto from_regs = [&](int ti) { return __builtin_bit_cast(bf16x8, breg[ti][KS]); };
+                if constexpr (KS == 0) base_block(0, std::true_type{}, from_regs);
+                else if (KS < ks_count) base_block(KS, std::false_type{}, from_regs);       // wave-uniform
+            });
+        } else {
+            auto from_memory = [&](int ks) {
+                return [&, ks](int ti) {
+                    if constexpr (BGLOBAL)
+                        return __builtin_bit_cast(bf16x8, g_ptable[slot][min(wave * TPW + ti, kMaxTiles - 1) * kMaxKs + ks][lane]);
+                    else
+                        return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(bsm + ((size_t)(ti * ks_count + ks) * 64 + lane) * 16));
+                };
+            };
+            base_block(0, std::true_type{}, from_memory(0));
+            for (int ks = 1; ks < ks_count; ++ks) base_block(ks, std::false_type{}, from_memory(ks));
+        }
 
         if constexpr (!F32IN) {
             // every wave has read the token out of LDS: refill the buffer with the next token now
@@ -608,7 +632,7 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
     wait_all_vm();
 }
 
-template <int KLOG2, int TPW, bool F32IN, int OUT, bool BGLOBAL = false>
+template <int KLOG2, int TPW, bool F32IN, int OUT, bool BGLOBAL = false, int KSREG = 0>
 pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     using L = Layout<KLOG2>;
     constexpr int NS = F32IN ? 3 : 1;
@@ -620,7 +644,8 @@ pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     pme_status st = PME_OK;
     const int slot = table_slot(a.b >> a.fold, a.fold, rows, a.stream, &st);
     if (slot < 0) return st;
-    auto kern = k_rotate_mfma<KLOG2, TPW, F32IN, OUT, false, BGLOBAL>;
+    if (KSREG > 0 && ks > KSREG) return PME_ERR_UNSUPPORTED_PATH;
+    auto kern = k_rotate_mfma<KLOG2, TPW, F32IN, OUT, false, BGLOBAL, KSREG>;
     // the same kernel runs with different LDS sizes (they follow the shape): allow the largest one accepted above
     static std::atomic<uint32_t> done;
     if (lds > 48 * 1024 && allow_dynamic_lds(kern, (int)kMaxDynLds, done) != PME_OK) return PME_ERR_HIP;
@@ -668,12 +693,12 @@ pme_status launch_multi(const RotateArgs& a, int ks) {
     return launch_multi_out<KLOG2, TPW, OUT_SYM>(a, ks);
 }
 
-template <int KLOG2, int TPW, bool F32IN, bool BGLOBAL = false>
+template <int KLOG2, int TPW, bool F32IN, bool BGLOBAL = false, int KSREG = 0>
 pme_status launch_one(const RotateArgs& a, int ks, int nwaves) {
-    if (a.xhat) return launch_out<KLOG2, TPW, F32IN, OUT_XHAT, BGLOBAL>(a, ks, nwaves);
-    if (a.ex) return launch_out<KLOG2, TPW, F32IN, OUT_MXFP4, BGLOBAL>(a, ks, nwaves);
-    if (a.zx) return launch_out<KLOG2, TPW, F32IN, OUT_ASYM, BGLOBAL>(a, ks, nwaves);
-    return launch_out<KLOG2, TPW, F32IN, OUT_SYM, BGLOBAL>(a, ks, nwaves);
+    if (a.xhat) return launch_out<KLOG2, TPW, F32IN, OUT_XHAT, BGLOBAL, KSREG>(a, ks, nwaves);
+    if (a.ex) return launch_out<KLOG2, TPW, F32IN, OUT_MXFP4, BGLOBAL, KSREG>(a, ks, nwaves);
+    if (a.zx) return launch_out<KLOG2, TPW, F32IN, OUT_ASYM, BGLOBAL, KSREG>(a, ks, nwaves);
+    return launch_out<KLOG2, TPW, F32IN, OUT_SYM, BGLOBAL, KSREG>(a, ks, nwaves);
 }
 
 int g_tpw_override = 0;
@@ -723,12 +748,17 @@ pme_status launch_rotate_mfma(const RotateArgs& in) {
     //  * the order-312 and order-344 blocks (19968 = 312 x 64, 22016 = 344 x 64): 20 and 22 column tiles on 10
     //    and 8 waves, about 150 KB of fragments that do not fit in LDS beside the token at all;
     //  * 2^k = 128 (8704): 4 % faster.
+    // Where a wave's fragments are few (TPW x K steps <= 8 registers of 16 bytes), it reads them once and keeps
+    // them in registers for all its tokens: another 3-6 % (8448 .. 9728, 8704, 15360).
     if (!f32 && g_tpw_override == 0) {
         if (a.k == 6 && nt >= 8) {
+            if (nt <= 2 * kMaxWaves && ks <= 4) return launch_one<6, 2, false, true, 4>(a, ks, (nt + 1) / 2);
             if (nt <= 2 * kMaxWaves) return launch_one<6, 2, false, true>(a, ks, (nt + 1) / 2);
             return launch_one<6, 3, false, true>(a, ks, (nt + 2) / 3);
         }
+        if (a.k == 7 && tpw == 2 && ks <= 2) return launch_one<7, 2, false, true, 2>(a, ks, (nt + 1) / 2);
         if (a.k == 7 && tpw == 2) return launch_one<7, 2, false, true>(a, ks, (nt + 1) / 2);
+        if (a.k == 8 && tpw == 1 && ks <= 2) return launch_one<8, 1, false, true, 2>(a, ks, nt);
     }
     const int nwaves = (nt + tpw - 1) / tpw;
     if (nwaves > kMaxWaves) return PME_ERR_UNSUPPORTED_PATH;
