@@ -29,6 +29,9 @@
  *    the asymmetric activation variant).
  *  - Rows of packed codes are dense: the row pitch is d_e / 2 bytes.
  *  - Outputs must not alias inputs.
+ *  - Size limits: T and N below 2^31, d_e at most 2^20 (PME_ERR_SHAPE beyond).  Operands of any byte size within
+ *    those limits are accepted; a GEMM whose packed activations or weights exceed 4 GiB is enqueued as several
+ *    launches over slices of tokens or output channels, with the same results.
  */
 #ifndef PME_H
 #define PME_H

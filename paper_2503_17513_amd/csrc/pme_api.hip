@@ -59,8 +59,11 @@ pme_status check_gemm(const uint8_t* qx, const uint8_t* qw, int64_t T, int64_t d
     return PME_OK;
 }
 
-pme_status run_gemm(const pme::GemmArgs& a) {
-    if (a.T == 0 || a.N == 0) return PME_OK;
+// Rows of an operand the matrix-core kernels can address with their 32-bit byte offsets, as a multiple of the
+// largest tile edge so that a slice starts on a tile (and vector-store) boundary.
+int64_t max_slice_rows(int64_t row_bytes) { return std::max<int64_t>(256, (((int64_t(1) << 32) - 1) / row_bytes) & ~int64_t(255)); }
+
+pme_status run_gemm_slice(const pme::GemmArgs& a) {
     int path = g_path.load();
     if (path != PME_PATH_GENERIC) {
         // few tokens: the weight-streaming kernel, unless the output is wide enough to fill the chip with tiles
@@ -70,6 +73,29 @@ pme_status run_gemm(const pme::GemmArgs& a) {
         if (s != PME_ERR_UNSUPPORTED_PATH || path == PME_PATH_MFMA) return s;
     }
     return pme::launch_gemm_generic(a);
+}
+
+// Operands beyond 4 GiB go through the same kernels in slices of tokens (and of output channels).
+pme_status run_gemm(const pme::GemmArgs& a) {
+    if (a.T == 0 || a.N == 0) return PME_OK;
+    const int64_t kb = a.d_e / 2, rows = max_slice_rows(kb), esz = a.out_i32 ? 4 : 2;
+    if (a.T <= rows && a.N <= rows) return run_gemm_slice(a);
+    for (int64_t t0 = 0; t0 < a.T; t0 += rows)
+        for (int64_t n0 = 0; n0 < a.N; n0 += rows) {
+            pme::GemmArgs p = a;
+            p.T = std::min(rows, a.T - t0);
+            p.N = std::min(rows, a.N - n0);
+            p.qx = a.qx + t0 * kb;
+            p.qw = a.qw + n0 * kb;
+            if (a.sx) p.sx = a.sx + t0;
+            if (a.sw) p.sw = a.sw + n0;
+            if (a.zx) p.zx = a.zx + t0;
+            if (a.wsum) p.wsum = a.wsum + n0;
+            p.y = static_cast<unsigned char*>(a.y) + (t0 * a.ldy + n0) * esz;
+            const pme_status s = run_gemm_slice(p);
+            if (s != PME_OK) return s;
+        }
+    return PME_OK;
 }
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -230,8 +256,7 @@ pme_status pme_hadamard_expand_quant_mxfp4(const void* x, pme_dtype xt, int64_t 
     return run_rotate(a);
 }
 
-static pme_status run_mxgemm(const pme::MxGemmArgs& a) {
-    if (a.T == 0 || a.N == 0) return PME_OK;
+static pme_status run_mxgemm_slice(const pme::MxGemmArgs& a) {
     int path = g_path.load();
     if (path != PME_PATH_GENERIC) {
         // few tokens: the weight-streaming kernel, unless the output is wide enough to fill the chip with tiles
@@ -241,6 +266,26 @@ static pme_status run_mxgemm(const pme::MxGemmArgs& a) {
         if (s != PME_ERR_UNSUPPORTED_PATH || path == PME_PATH_MFMA) return s;
     }
     return pme::launch_mxgemm_generic(a);
+}
+
+static pme_status run_mxgemm(const pme::MxGemmArgs& a) {
+    if (a.T == 0 || a.N == 0) return PME_OK;
+    const int64_t kb = a.d_e / 2, eb = a.d_e / 32, rows = max_slice_rows(kb);
+    if (a.T <= rows && a.N <= rows) return run_mxgemm_slice(a);
+    for (int64_t t0 = 0; t0 < a.T; t0 += rows)
+        for (int64_t n0 = 0; n0 < a.N; n0 += rows) {
+            pme::MxGemmArgs p = a;
+            p.T = std::min(rows, a.T - t0);
+            p.N = std::min(rows, a.N - n0);
+            p.qx = a.qx + t0 * kb;
+            p.ex = a.ex + t0 * eb;
+            p.qw = a.qw + n0 * kb;
+            p.ew = a.ew + n0 * eb;
+            p.y = static_cast<unsigned char*>(a.y) + (t0 * a.ldy + n0) * 2;
+            const pme_status s = run_mxgemm_slice(p);
+            if (s != PME_OK) return s;
+        }
+    return PME_OK;
 }
 
 pme_status pme_mxfp4_gemm(const uint8_t* qx, const uint8_t* ex, const uint8_t* qw, const uint8_t* ew,

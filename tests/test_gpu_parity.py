@@ -39,7 +39,8 @@ ROTATE_CASES = [
     ("f32_b132_k6", 3, 8192, 8448, "f32", (GENERIC, MFMA)),
     ("pow2_ratio_one", 5, 256, 256, "bf16", (GENERIC, MFMA)),
     ("pow2_padded", 5, 200, 256, "f32", (GENERIC, MFMA)),
-    # 2^k > 512: the matrix-core kernel folds the first k - 9 butterfly stages into the base block
+    # 2^k > 128 with a small block (required beyond 512): the matrix-core kernel folds the first butterfly stages
+    # into the base block (4096 runs as 32 x 128, 12288 as 48 x 256, 32768 as 64 x 512, 40960 as 80 x 512)
     ("pow2_k12", 3, 4096, 4096, "bf16", (GENERIC, MFMA)),
     ("pow2_k10_ragged_d", 5, 1000, 1024, "bf16", (GENERIC, MFMA)),
     ("pow2_k13_f32", 3, 8192, 8192, "f32", (GENERIC, MFMA)),
