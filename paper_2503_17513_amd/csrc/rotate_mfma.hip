@@ -1,4 +1,5 @@
-// Rotate + quantize on the matrix cores: one workgroup per token.
+// Rotate + quantize on the matrix cores: one workgroup per token (one wave per token where a token is a
+// single wave's work, see MULTI below).
 //
 // Per token (paper Section 3, X_hat = X H_hat, H = P_b (x) S_{2^k}, index i = a 2^k + c):
 //   1. the token's d inputs are loaded once, coalesced, and laid out in LDS as bf16 MFMA
@@ -16,11 +17,14 @@
 //   5. codes by one fused multiply-add with a rounding constant (round half to even),
 //      packed eight to a dword and stored in runs of 2^(k-3) bytes per lane.
 // Waves split the token by a' (16-wide tiles, TPW tiles per wave); the FWHT never crosses a'.
+// Since S_{2^k} = S_{2^f} (x) S_{2^(k-f)}, the launcher may hand the kernel the same H as a larger block
+// P_b (x) S_{2^f} times fewer columns (see launch_rotate_mfma): steps 2 and 3 are unaware of it.
 #include "pme_internal.h"
 
 #include <algorithm>
 #include <mutex>
 #include <type_traits>
+#include <vector>
 
 namespace pme {
 namespace {
@@ -30,7 +34,7 @@ typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
 typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(2))) uint32_t u32x2;
 
-constexpr int kMaxWaves = 10;   // b <= 152 -> at most 10 tiles of 16 columns
+constexpr int kMaxWaves = 10;   // waves per workgroup: 10 column tiles of 16 (order 160) at one tile per wave
 
 template <int KLOG2> struct Layout {
     static constexpr int NC = 1 << KLOG2;      // FWHT length
@@ -144,17 +148,20 @@ __device__ __forceinline__ uint32_t split_hi(float f, float& rem) {
 
 // ---------------------------------------------------------------------------------------------
 // B-operand table: the Paley block as ready-made bf16 MFMA fragments, built once per
-// (device, b, real base rows) by a small kernel and kept in device memory owned by the library.
+// (device, b, folded stages, real base rows) by a small kernel and kept in device memory owned by the library.
 // Entry (tile, ks), lane (a' = 16 tile + lane % 16, g = lane / 16) holds P[32 ks + 8 g + e][a'],
 // e = 0..7 (+-1 in bf16; 0 outside the block or beyond the rows that hold real inputs).
 // ---------------------------------------------------------------------------------------------
-constexpr int kMaxTiles = 22, kMaxKs = 7, kSlots = 8;     // blocks up to order 352, up to 224 real base rows
-__device__ __align__(256) u32x4 g_ptable[kSlots][kMaxTiles * kMaxKs][64];
+constexpr int kMaxTiles = 22, kMaxKs = 7;     // blocks up to order 352, up to 224 real base rows
+constexpr int kPoolEntries = 16384;           // 16 MB of fragments per device: a shape takes 7 to 154 KB of it
+typedef u32x4 Fragment[64];                   // one 16 x 32 B-operand tile: 16 bytes per lane
+__device__ __align__(256) Fragment g_fragment_pool[kPoolEntries];
 
 // Fragments of the base block B = P_b (x) S_{2^fold} of order b 2^fold (fold = 0: the Paley block itself).
 // Folding the first `fold` butterfly stages into the block leaves H = P_b (x) S_{2^k} unchanged, since
 // S_{2^k} = S_{2^fold} (x) S_{2^(k - fold)}: entry ((a, u), (a', u')) = P[a][a'] (-1)^popcount(u & u').
-__global__ void __launch_bounds__(64) k_fill_ptable(int slot, int b, int fold, int rows) {
+// One workgroup per (tile, ks); table[tile * kMaxKs + ks] is the fragment.
+__global__ void __launch_bounds__(64) k_fill_ptable(Fragment* table, int b, int fold, int rows) {
     __shared__ signed char chi[512];
     const int lane = threadIdx.x, q = b - 1, border = b << fold, umask = (1 << fold) - 1;
     if (b > 1) fill_quadratic_character(chi, q, lane, 64);
@@ -177,33 +184,45 @@ __global__ void __launch_bounds__(64) k_fill_ptable(int slot, int b, int fold, i
         }
         pk[p] = word;
     }
-    g_ptable[slot][blockIdx.x][lane] = pk;
+    table[blockIdx.x][lane] = pk;
 }
 
-struct TableKey { int device, b, fold, rows; };
+struct TableKey { int b, fold, rows; Fragment* table; };
+struct DeviceTables {
+    Fragment* pool = nullptr;          // this device's copy of g_fragment_pool
+    int used = 0;                      // entries handed out
+    std::vector<TableKey> keys;
+};
+constexpr int kMaxDevices = 16;
 std::mutex g_table_mutex;
-TableKey g_table_keys[kSlots];
-int g_table_used = 0, g_table_next = 0;
+DeviceTables g_tables[kMaxDevices];
 
-// Returns the slot holding the table for (b, fold, rows) on the current device, building it on a miss.
-// A miss launches the fill kernel on `stream` and waits for it once, so that callers on other
-// streams never see a half-written table.  With more than kSlots live shapes per process the
-// oldest slot is reused; calls still in flight on that shape would then race with the refill.
-int table_slot(int b, int fold, int rows, hipStream_t stream, pme_status* st) {
+// Returns the fragment table for (b, fold, rows) on the current device, building it on a miss: ceil(order / 16)
+// tiles of kMaxKs fragments from the device's pool.  A miss launches the fill kernel on `stream` and waits for
+// it once, so that callers on other streams never see a half-written table.  Tables are never moved or
+// reused: kernels in flight, and HIP graphs that captured a launch, keep reading them.  When the pool is
+// used up (hundreds of distinct shapes in one process) a further shape gets PME_ERR_UNSUPPORTED_PATH and the
+// automatic path takes the generic kernel for it.
+const Fragment* fragment_table(int b, int fold, int rows, hipStream_t stream, pme_status* st) {
     int dev = 0;
-    if (hipGetDevice(&dev) != hipSuccess) { *st = PME_ERR_HIP; return -1; }
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) { *st = PME_ERR_HIP; return nullptr; }
     std::lock_guard<std::mutex> lock(g_table_mutex);
-    for (int i = 0; i < g_table_used; ++i)
-        if (g_table_keys[i].device == dev && g_table_keys[i].b == b && g_table_keys[i].fold == fold &&
-            g_table_keys[i].rows == rows)
-            return i;
-    const int slot = g_table_next;
-    hipLaunchKernelGGL(k_fill_ptable, dim3(kMaxTiles * kMaxKs), dim3(64), 0, stream, slot, b, fold, rows);
-    if (hipGetLastError() != hipSuccess || hipStreamSynchronize(stream) != hipSuccess) { *st = PME_ERR_HIP; return -1; }
-    g_table_keys[slot] = TableKey{dev, b, fold, rows};
-    g_table_next = (g_table_next + 1) % kSlots;
-    if (g_table_used < kSlots) ++g_table_used;
-    return slot;
+    DeviceTables& D = g_tables[dev];
+    for (const TableKey& e : D.keys)
+        if (e.b == b && e.fold == fold && e.rows == rows) return e.table;
+    if (!D.pool && hipGetSymbolAddress(reinterpret_cast<void**>(&D.pool), HIP_SYMBOL(g_fragment_pool)) != hipSuccess) {
+        D.pool = nullptr;
+        *st = PME_ERR_HIP;
+        return nullptr;
+    }
+    const int tiles = ((b << fold) + 15) / 16, entries = tiles * kMaxKs;
+    if (D.used + entries > kPoolEntries) { *st = PME_ERR_UNSUPPORTED_PATH; return nullptr; }
+    Fragment* table = D.pool + D.used;
+    hipLaunchKernelGGL(k_fill_ptable, dim3(entries), dim3(64), 0, stream, table, b, fold, rows);
+    if (hipGetLastError() != hipSuccess || hipStreamSynchronize(stream) != hipSuccess) { *st = PME_ERR_HIP; return nullptr; }
+    D.used += entries;
+    D.keys.push_back(TableKey{b, fold, rows, table});
+    return table;
 }
 
 #define PME_AS1 __attribute__((address_space(1)))
@@ -249,7 +268,7 @@ enum { OUT_SYM = 0, OUT_ASYM = 1, OUT_XHAT = 2, OUT_MXFP4 = 3 };   // int4 symme
 // loop, and keeps them in registers.
 template <int KLOG2, int TPW, bool F32IN, int OUT, bool MULTI = false, bool BGLOBAL = false, int KSREG = 0>
 __global__ void __launch_bounds__((64 * max_waves<KLOG2, TPW>()))
-k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, int b, int ks_count, int slot,
+k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, int b, int ks_count, const Fragment* __restrict__ ptable,
               double gamma, uint8_t* __restrict__ qx, float* __restrict__ sx, int32_t* __restrict__ zx,
               uint8_t* __restrict__ ex, float* __restrict__ xhat) {
     using L = Layout<KLOG2>;
@@ -265,6 +284,7 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
     // the waves that share a token, and this thread's place among them
     const int wave = MULTI ? 0 : wave_hw, nwaves = MULTI ? 1 : nwaves_hw;
     const int tid = MULTI ? lane : (int)threadIdx.x, nthreads = MULTI ? 64 : (int)blockDim.x;
+    const int last_tile = (b + 15) / 16 - 1;          // surplus tile slots of the last wave re-read it
     const int l15 = lane & 15, g = lane >> 4;
     const int rows_k = 32 * ks_count;                 // rows of the K-padded operand
     unsigned char* tsm = smem + (MULTI ? (size_t)wave_hw * NS * plane_bytes : 0);          // this token's planes
@@ -353,21 +373,21 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
         for (int ti = 0; ti < TPW; ++ti)
 #pragma unroll
             for (int ks = 0; ks < KSREG; ++ks)
-                breg[ti][ks] = g_ptable[slot][min(wave * TPW + ti, kMaxTiles - 1) * kMaxKs + min(ks, ks_count - 1)][lane];
+                breg[ti][ks] = ptable[min(wave * TPW + ti, last_tile) * kMaxKs + min(ks, ks_count - 1)][lane];
     } else if constexpr (BGLOBAL) {
         // nothing to stage
     } else if constexpr (MULTI) {
         for (int f = wave_hw; f < TPW * ks_count; f += nwaves_hw) {       // fragment f = ti ks_count + ks
-            const int tile = min(f / ks_count, kMaxTiles - 1);
-            *reinterpret_cast<u32x4*>(bsm + ((size_t)f * 64 + lane) * 16) = g_ptable[slot][tile * kMaxKs + f % ks_count][lane];
+            const int tile = min(f / ks_count, last_tile);
+            *reinterpret_cast<u32x4*>(bsm + ((size_t)f * 64 + lane) * 16) = ptable[tile * kMaxKs + f % ks_count][lane];
         }
         lds_barrier();                      // the only workgroup barrier: every wave passes it exactly once
     } else {
 #pragma unroll
         for (int ti = 0; ti < TPW; ++ti) {
-            const int tile = min(wave * TPW + ti, kMaxTiles - 1);
+            const int tile = min(wave * TPW + ti, last_tile);
             for (int ks = 0; ks < ks_count; ++ks)
-                *reinterpret_cast<u32x4*>(bsm + ((size_t)(ti * ks_count + ks) * 64 + lane) * 16) = g_ptable[slot][tile * kMaxKs + ks][lane];
+                *reinterpret_cast<u32x4*>(bsm + ((size_t)(ti * ks_count + ks) * 64 + lane) * 16) = ptable[tile * kMaxKs + ks][lane];
         }
     }
     // Synchronisation among the waves that share a token: a barrier, or for a single wave only a wait for
@@ -438,7 +458,7 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
             auto from_memory = [&](int ks) {
                 return [&, ks](int ti) {
                     if constexpr (BGLOBAL)
-                        return __builtin_bit_cast(bf16x8, g_ptable[slot][min(wave * TPW + ti, kMaxTiles - 1) * kMaxKs + ks][lane]);
+                        return __builtin_bit_cast(bf16x8, ptable[min(wave * TPW + ti, last_tile) * kMaxKs + ks][lane]);
                     else
                         return __builtin_bit_cast(bf16x8, *reinterpret_cast<const u32x4*>(bsm + ((size_t)(ti * ks_count + ks) * 64 + lane) * 16));
                 };
@@ -642,8 +662,8 @@ pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     if (lds > kMaxDynLds || nwaves > max_waves<KLOG2, TPW>()) return PME_ERR_UNSUPPORTED_PATH;
     const int rows = (int)((a.d + L::NC - 1) >> KLOG2);
     pme_status st = PME_OK;
-    const int slot = table_slot(a.b >> a.fold, a.fold, rows, a.stream, &st);
-    if (slot < 0) return st;
+    const Fragment* ptable = fragment_table(a.b >> a.fold, a.fold, rows, a.stream, &st);
+    if (!ptable) return st;
     if (KSREG > 0 && ks > KSREG) return PME_ERR_UNSUPPORTED_PATH;
     auto kern = k_rotate_mfma<KLOG2, TPW, F32IN, OUT, false, BGLOBAL, KSREG>;
     // the same kernel runs with different LDS sizes (they follow the shape): allow the largest one accepted above
@@ -657,7 +677,7 @@ pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     const unsigned grid = (unsigned)std::min<int64_t>(a.T, 256 * (int64_t)occ);
     const double gamma = 1.0 / sqrt((double)a.d_e);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * nwaves), lds, a.stream, a.x, a.ldx, (int)a.T, (int)a.d,
-                       (int)a.d_e, a.b, ks, slot, gamma, a.qx, a.sx, a.zx, a.ex, a.xhat);
+                       (int)a.d_e, a.b, ks, ptable, gamma, a.qx, a.sx, a.zx, a.ex, a.xhat);
     return hip_status(hipGetLastError());
 }
 
@@ -672,8 +692,8 @@ pme_status launch_multi_out(const RotateArgs& a, int ks) {
     if (lds > kMaxDynLds) return PME_ERR_UNSUPPORTED_PATH;
     const int rows = (int)((a.d + L::NC - 1) >> KLOG2);
     pme_status st = PME_OK;
-    const int slot = table_slot(a.b >> a.fold, a.fold, rows, a.stream, &st);
-    if (slot < 0) return st;
+    const Fragment* ptable = fragment_table(a.b >> a.fold, a.fold, rows, a.stream, &st);
+    if (!ptable) return st;
     auto kern = k_rotate_mfma<KLOG2, TPW, false, OUT, true, (KSREG > 0), KSREG>;
     static std::atomic<uint32_t> done;
     if (lds > 48 * 1024 && allow_dynamic_lds(kern, (int)kMaxDynLds, done) != PME_OK) return PME_ERR_HIP;
@@ -683,7 +703,7 @@ pme_status launch_multi_out(const RotateArgs& a, int ks) {
     const unsigned grid = (unsigned)std::min<int64_t>(groups, 256 * (int64_t)occ);
     const double gamma = 1.0 / sqrt((double)a.d_e);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * kMultiWaves), lds, a.stream, a.x, a.ldx, (int)a.T, (int)a.d,
-                       (int)a.d_e, a.b, ks, slot, gamma, a.qx, a.sx, a.zx, a.ex, a.xhat);
+                       (int)a.d_e, a.b, ks, ptable, gamma, a.qx, a.sx, a.zx, a.ex, a.xhat);
     return hip_status(hipGetLastError());
 }
 template <int KLOG2, int TPW, int KSREG>
