@@ -405,6 +405,51 @@ def test_forced_mfma_path_refuses_unsupported_shape():
         pme.w4a4_gemm_i32(q, q)               # d_e = 80 is not a multiple of 128
 
 
+_POOL_SCRIPT = """
+import sys, torch
+sys.path.insert(0, sys.argv[1])
+import paper_2503_17513_amd as pme
+torch.manual_seed(0)
+x = torch.randn(2, 152 * 64, device="cuda").to(torch.bfloat16)
+pme.set_path(pme.PATH_MFMA)
+first = pme.hadamard_expand_quant(x[:, :64].contiguous(), 9728)
+served, refused = 0, None
+for d_e, b in ((9728, 152), (8960, 140)):          # every count of real base rows is a table of its own
+    for rows in range(1, b + 1):
+        try:
+            pme.hadamard_expand_quant(x[:, :64 * rows].contiguous(), d_e)
+            served += 1
+        except pme.PmeError as e:
+            assert e.status == 8, e.status
+            refused = (64 * rows, d_e)
+            break
+    if refused:
+        break
+assert refused is not None and served > 200, (served, refused)
+xs = x[:, :refused[0]].contiguous()
+pme.set_path(pme.PATH_AUTO)
+qa, sa = pme.hadamard_expand_quant(xs, refused[1])
+pme.set_path(pme.PATH_GENERIC)
+qg, sg = pme.hadamard_expand_quant(xs, refused[1])
+assert torch.equal(qa, qg) and torch.equal(sa, sg)
+pme.set_path(pme.PATH_MFMA)                          # tables handed out earlier keep working
+again = pme.hadamard_expand_quant(x[:, :64].contiguous(), 9728)
+torch.cuda.synchronize()
+assert torch.equal(again[0], first[0]) and torch.equal(again[1], first[1])
+print("POOL_OK", served)
+"""
+
+
+def test_fragment_pool_exhaustion_falls_back_to_the_generic_kernel():
+    # in a process of its own: the pool is never given back, and the other tests need it
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, "-c", _POOL_SCRIPT, root], capture_output=True, text=True, timeout=110)
+    assert r.returncode == 0 and "POOL_OK" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
+
+
 def test_layer_in_a_hip_graph_replays_identically():
     # the library only enqueues kernels (no memset nodes, no allocation, no synchronisation once a shape is
     # warm), so a captured layer call must give the eager result on every replay, with eager work between
