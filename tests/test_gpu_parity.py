@@ -283,7 +283,11 @@ def test_gemm_asymmetric(path, T):
 
 
 LAYER_CASES = [("C1", None), ("mid_b68_k5", (300, 2048, 2176, 520)), ("mid_b132_k6", (8, 8192, 8448, 2048)),
-               ("mid_b60_k8", (130, 14336, 15360, 260))]
+               ("mid_b60_k8", (130, 14336, 15360, 260)),
+               # decode: at most 16 tokens through the fused call (weight-streaming GEMM)
+               ("decode_b68_k7", (16, 8192, 8704, 530)), ("decode_b60_k8_one_token", (1, 14336, 15360, 300)),
+               ("decode_b132_k5", (5, 4096, 4224, 200)), ("decode_folded_b20_k9", (3, 8192, 10240, 100)),
+               ("decode_folded_b12_k10", (4, 8192, 12288, 64)), ("decode_b152_k6_ragged_d", (9, 8000, 9728, 1000))]
 
 
 @pytest.mark.parametrize("name,shape", LAYER_CASES, ids=[c[0] for c in LAYER_CASES])
@@ -450,21 +454,42 @@ def test_fragment_pool_exhaustion_falls_back_to_the_generic_kernel():
     assert r.returncode == 0 and "POOL_OK" in r.stdout, r.stdout[-2000:] + r.stderr[-2000:]
 
 
-def test_layer_in_a_hip_graph_replays_identically():
-    # the library only enqueues kernels (no memset nodes, no allocation, no synchronisation once a shape is
-    # warm), so a captured layer call must give the eager result on every replay, with eager work between
-    wl = make_workload(custom_spec(300, 2048, 2176, 520, seed=5))
+def test_decode_layer_calls_sharing_a_workspace():
+    # back-to-back decode calls with changing token counts on one workspace: each equals the chain of its parts
+    d, d_e, N = 8192, 8448, 1000
+    wl = make_workload(custom_spec(16, d, d_e, N, act_dist="student_t3", seed=9))
     x = torch.from_numpy(wl.x).to(torch.bfloat16).cuda()
     qw = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
     sw = torch.from_numpy(wl.sw).cuda()
-    y_eager = pme.expanded_linear(x, 2176, qw, sw).clone()           # also warms the shape
-    ws = torch.empty((pme.workspace_bytes(300, 2048, 2176, 520),), dtype=torch.uint8, device="cuda")
+    ws = torch.empty((pme.workspace_bytes(16, d, d_e, N),), dtype=torch.uint8, device="cuda")
+    for T in (16, 3, 16, 1, 8, 8):
+        xt = x[:T].contiguous()
+        y = torch.full((T, N), float("nan"), dtype=torch.bfloat16, device="cuda")
+        pme.expanded_linear(xt, d_e, qw, sw, y, ws)
+        qx, sx = pme.hadamard_expand_quant(xt, d_e)
+        y_parts = pme.w4a4_gemm(qx, sx, qw, sw)
+        torch.cuda.synchronize()
+        assert torch.equal(y.view(torch.int16), y_parts.view(torch.int16)), f"T = {T}"
+
+
+@pytest.mark.parametrize("shape", ((300, 2048, 2176, 520), (8, 8192, 8448, 2048)), ids=("prefill", "decode"))
+def test_layer_in_a_hip_graph_replays_identically(shape):
+    # the library only enqueues kernels (no memset nodes, no allocation, no synchronisation once a shape is
+    # warm), so a captured layer call must give the eager result on every replay, with eager work between
+    T, d, d_e, N = shape
+    wl = make_workload(custom_spec(T, d, d_e, N, seed=5))
+    x = torch.from_numpy(wl.x).to(torch.bfloat16).cuda()
+    qw = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+    sw = torch.from_numpy(wl.sw).cuda()
+    ws = torch.empty((pme.workspace_bytes(T, d, d_e, N),), dtype=torch.uint8, device="cuda")
+    y_eager = torch.zeros((T, N), dtype=torch.bfloat16, device="cuda")
+    pme.expanded_linear(x, d_e, qw, sw, y_eager, ws)                 # also warms the shape (and this workspace)
     y = torch.zeros_like(y_eager)
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
     g = torch.cuda.CUDAGraph()
     with torch.cuda.graph(g, stream=side):
-        pme.expanded_linear(x, 2176, qw, sw, y, ws)
+        pme.expanded_linear(x, d_e, qw, sw, y, ws)
     for rep in range(4):
         y.fill_(float("nan"))                                        # eager work on the outputs between replays
         ws.zero_()
