@@ -264,6 +264,8 @@ def main() -> int:
         "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms, "plain_loop_ms_per_step": plain_ms, "wall_ms_per_step": wall_ms,
+        # the same time priced at the unexpanded layer's 2 T d N operations (what the expansion costs in useful work)
+        "effective_tops_unexpanded": 2.0 * sp.T * sp.d * sp.N / (ms * 1e-3) / 1e12,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{sp.name}: T={sp.T} d={sp.d} d_e={sp.d_e} N={sp.N} in={sp.in_dtype}",

@@ -110,6 +110,26 @@ def test_rotate_strided_rows(path):
     check_xhat(pme.hadamard_expand_f32(xd, d_e).cpu().numpy(), ref)
 
 
+@pytest.mark.parametrize("d_h,d_he", ((64, 80), (128, 160), (128, 192)))
+def test_per_head_expansion_of_the_value_and_output_projections(d_h, d_he):
+    # Section 4, compute graph details: the head-wise rotation between the value and output projections is merged
+    # into their weights, so expanding it is weight-side work only: each head's d_h columns of W_v and of W_o^T
+    # (slices of wider matrices, hence the row pitch) go through X H_hat, and the product of the pair is unchanged
+    d_model, heads = 192, 3
+    rng = np.random.default_rng(7)
+    wv = rng.standard_normal((d_model, heads * d_h)).astype(np.float32)          # x W_v: head h = columns h d_h ..
+    wo_t = rng.standard_normal((d_model, heads * d_h)).astype(np.float32)        # W_o^T, same column layout
+    wv_d, wo_d = torch.from_numpy(wv).cuda(), torch.from_numpy(wo_t).cuda()
+    for h in range(heads):
+        cols = slice(h * d_h, (h + 1) * d_h)
+        a = pme.hadamard_expand_f32(wv_d[:, cols], d_he).cpu().numpy()
+        b = pme.hadamard_expand_f32(wo_d[:, cols], d_he).cpu().numpy()
+        check_xhat(a, oracle.rotate_structured(wv[:, cols], d_he))
+        check_xhat(b, oracle.rotate_structured(wo_t[:, cols], d_he))
+        exact = wv[:, cols].astype(np.float64) @ wo_t[:, cols].astype(np.float64).T
+        assert np.max(np.abs(a.astype(np.float64) @ b.astype(np.float64).T - exact)) <= 1e-5 * np.max(np.abs(exact))
+
+
 ASYM_CASES = [("tiny", 16, 64, 80, "f32", (GENERIC,)), ("b68_k5", 9, 2048, 2176, "bf16", (GENERIC, MFMA)),
               ("b60_k8", 4, 14336, 15360, "bf16", (GENERIC, MFMA)),
               ("b68_k5_token_per_wave", 1026, 2048, 2176, "bf16", (MFMA,)),
