@@ -669,10 +669,12 @@ pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     // the same kernel runs with different LDS sizes (they follow the shape): allow the largest one accepted above
     static std::atomic<uint32_t> done;
     if (lds > 48 * 1024 && allow_dynamic_lds(kern, (int)kMaxDynLds, done) != PME_OK) return PME_ERR_HIP;
-    // Persistent grid: as many workgroups as fit on the 256 compute units at once (LDS, and about 12
-    // waves per compute unit at this register use), preferring a count that divides the tokens evenly.
+    // Persistent grid: as many workgroups as fit on the 256 compute units at once: LDS, and 16 waves per
+    // compute unit (measured: 12 left memory latency exposed -- 8448 .. 9728, 18432 and 22016 ran 14-20 % slower
+    // -- and 20 is past what the registers admit); the four-wave workgroups of 2^k = 256 (15360) are the
+    // exception, 10 % faster at three per compute unit than at four.
     int occ = (int)((160 * 1024) / (lds + 1024));
-    occ = std::min(occ, 12 / nwaves);
+    occ = std::min(occ, (KLOG2 == 8 && nwaves == 4 ? 12 : 16) / nwaves);
     occ = std::max(1, std::min(occ, 8));
     const unsigned grid = (unsigned)std::min<int64_t>(a.T, 256 * (int64_t)occ);
     const double gamma = 1.0 / sqrt((double)a.d_e);
