@@ -781,7 +781,7 @@ pme_status launch_rotate_mfma(const RotateArgs& in) {
     // P fragments read from the table in device memory instead of LDS:
     //  * 2^k = 64 with 8 tiles or more (orders 132 .. 152: 8448, 8960, 9728): staging nt ks KB of fragments
     //    leaves room for only two workgroups per compute unit; without it the kernel measured 18 % faster;
-    //  * the order-312 and order-344 blocks (19968 = 312 x 64, 22016 = 344 x 64): 20 and 22 column tiles on 10
+    //  * the order-312 and order-344 blocks (19968 = 312 x 64, 22016 = 344 x 64): 20 and 22 column tiles on 7
     //    and 8 waves, about 150 KB of fragments that do not fit in LDS beside the token at all;
     //  * 2^k = 128 (8704): 4 % faster.
     // Where a wave's fragments are few (TPW x K steps <= 8 registers of 16 bytes), it reads them once and keeps
@@ -789,7 +789,9 @@ pme_status launch_rotate_mfma(const RotateArgs& in) {
     if (!f32 && g_tpw_override == 0) {
         if (a.k == 6 && nt >= 8) {
             if (nt <= 2 * kMaxWaves && ks <= 4) return launch_one<6, 2, false, true, 4>(a, ks, (nt + 1) / 2);
-            if (nt <= 2 * kMaxWaves) return launch_one<6, 2, false, true>(a, ks, (nt + 1) / 2);
+            // beyond 16 tiles three per wave: 7 waves for the order-312 block, so that two workgroups share a compute
+            // unit (19968: 42 -> 36 us for 2048 tokens against 10 waves of two tiles)
+            if (nt <= 16) return launch_one<6, 2, false, true>(a, ks, (nt + 1) / 2);
             return launch_one<6, 3, false, true>(a, ks, (nt + 2) / 3);
         }
         if (a.k == 7 && tpw == 2 && ks <= 2) return launch_one<7, 2, false, true, 2>(a, ks, (nt + 1) / 2);

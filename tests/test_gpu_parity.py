@@ -52,7 +52,7 @@ ROTATE_CASES = [
     ("b72_k5", 4, 2104, 2304, "bf16", (GENERIC, MFMA)),
     ("b140_k6", 3, 8192, 8960, "bf16", (GENERIC, MFMA)),
     ("b152_k6", 3, 8192, 9728, "bf16", (GENERIC, MFMA)),
-    # 20 column tiles on 10 waves, P fragments read from device memory
+    # 20 column tiles on 7 waves, P fragments read from device memory
     ("b312_k6", 3, 14336, 19968, "bf16", (GENERIC, MFMA)),
     ("b312_k6_many_tokens_ragged_d", 290, 14000, 19968, "bf16", (MFMA,)),
     ("b344_k6", 3, 14336, 22016, "bf16", (GENERIC, MFMA)),          # block over GF(7^3), 22 tiles on 8 waves
