@@ -343,9 +343,10 @@ def main() -> int:
         for _ in range(5):
             pme.expanded_linear_mxfp4(b["x"], sp.d_e, qw4, ew4, b["y"], b["ws"])
         it = max(20, args.steps)
-        t_l = _event_ms(lambda: pme.expanded_linear_mxfp4(b["x"], sp.d_e, qw4, ew4, b["y"], b["ws"]), it)
-        t_r = _event_ms(lambda: pme.hadamard_expand_quant_mxfp4(b["x"], sp.d_e), it)
-        t_g = _event_ms(lambda: pme.mxfp4_gemm(qx4, ex4, qw4, ew4, b["y"]), it)
+        layer_m = lambda: pme.expanded_linear_mxfp4(b["x"], sp.d_e, qw4, ew4, b["y"], b["ws"])
+        rot_m = lambda: pme.hadamard_expand_quant_mxfp4(b["x"], sp.d_e, qx4, ex4)
+        gemm_m = lambda: pme.mxfp4_gemm(qx4, ex4, qw4, ew4, b["y"])
+        t_l, t_r, t_g = (_graph_ms(f, it) or _event_ms(f, it, 5) for f in (layer_m, rot_m, gemm_m))
         out["mxfp4"] = {"layer_us": t_l * 1e3, "layer_tflops": ops / (t_l * 1e-3) / 1e12, "rotate_quant_us": t_r * 1e3,
                         "gemm_us": t_g * 1e3, "gemm_tflops": ops / (t_g * 1e-3) / 1e12, "gemm_peak_tflops": 10100.0,
                         "gemm_frac": ops / (t_g * 1e-3) / 1e12 / 10100.0, "gemm_traffic": None}

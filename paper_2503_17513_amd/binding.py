@@ -157,13 +157,18 @@ def expand_quantize_weights(wt: torch.Tensor, d_e: int):
     return qw, sw
 
 
-def hadamard_expand_quant_mxfp4(x: torch.Tensor, d_e: int):
-    """-> (packed E2M1 codes [T, d_e/2] uint8, E8M0 scale bytes [T, d_e/32] uint8)."""
+def hadamard_expand_quant_mxfp4(x: torch.Tensor, d_e: int, qx: torch.Tensor | None = None, ex: torch.Tensor | None = None):
+    """-> (packed E2M1 codes [T, d_e/2] uint8, E8M0 scale bytes [T, d_e/32] uint8); into qx, ex when given."""
     T, d, ldx = _rows(x)
-    qx = torch.empty((T, d_e // 2), dtype=torch.uint8, device=x.device)
-    ex = torch.empty((T, d_e // 32), dtype=torch.uint8, device=x.device)
-    _check(lib().pme_hadamard_expand_quant_mxfp4(_dev(x, "x"), _dtype_code(x), T, d, ldx, d_e, qx.data_ptr(),
-                                                 ex.data_ptr(), _stream()), "pme_hadamard_expand_quant_mxfp4")
+    if qx is None:
+        qx = torch.empty((T, d_e // 2), dtype=torch.uint8, device=x.device)
+    if ex is None:
+        ex = torch.empty((T, d_e // 32), dtype=torch.uint8, device=x.device)
+    if (qx.dtype != torch.uint8 or ex.dtype != torch.uint8 or tuple(qx.shape) != (T, d_e // 2) or tuple(ex.shape) != (T, d_e // 32)
+            or not qx.is_contiguous() or not ex.is_contiguous()):
+        raise ValueError("qx must be a contiguous uint8 [T, d_e/2] tensor and ex a contiguous uint8 [T, d_e/32] tensor")
+    _check(lib().pme_hadamard_expand_quant_mxfp4(_dev(x, "x"), _dtype_code(x), T, d, ldx, d_e, _dev(qx, "qx"),
+                                                 _dev(ex, "ex"), _stream()), "pme_hadamard_expand_quant_mxfp4")
     return qx, ex
 
 
