@@ -293,52 +293,62 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     load_frags(raw[1], smem, 1);
     unpack(raw[0], unp[0]);
     int cur = 0;                    // stage of K step kt
-    // K steps [k0, k1); whole: every K step whose DMA they issue is a full one
-    auto k_steps = [&](int k0, int k1, auto whole) {
-        for (int kt = k0; kt < k1; ++kt) {
-            const int nxt = (cur == NSTAGE - 1) ? 0 : cur + 1;
-            const unsigned char* scur = smem + cur * STAGE;
-            const unsigned char* snxt = smem + nxt * STAGE;
+    // One K step kt living in stage curc (an int, or an integral constant: then every LDS address of the step is a
+    // register plus an immediate); whole: the K step whose DMA it issues is a full one.
+    auto k_step = [&](int kt, auto curc, auto whole) {
+        const int cs = curc;
+        const int nxt = (cs == NSTAGE - 1) ? 0 : cs + 1;
+        const unsigned char* scur = smem + cs * STAGE;
+        const unsigned char* snxt = smem + nxt * STAGE;
 #pragma unroll
-            for (int s = 0; s < NSUB; ++s) {
-                if (s == NSUB - 2) {
-                    wait_vm<(NSTAGE - 2) * CH>();
-                    lds_barrier();      // stage nxt has landed for every wave; every wave has left stage cur
-                }
-                if (s + 2 < NSUB) load_frags(raw[s & 1], scur, s + 2);
-                else load_frags(raw[s & 1], snxt, s + 2 - NSUB);
-                if (s != NSUB - 2) {
-                    unpack(raw[(s + 1) & 1], unp[(s + 1) & 1]);
-                    mfma_all(unp[s & 1]);
-                    interleave(true);
-                } else {
-                    // the region after the barrier also refills stage cur with K step kt + NSTAGE, one DMA
-                    // instruction after each part of the matrix work
-                    const int ktn = min(kt + NSTAGE, KT - 1);
+        for (int s = 0; s < NSUB; ++s) {
+            if (s == NSUB - 2) {
+                wait_vm<(NSTAGE - 2) * CH>();
+                lds_barrier();      // stage nxt has landed for every wave; every wave has left stage cur
+            }
+            if (s + 2 < NSUB) load_frags(raw[s & 1], scur, s + 2);
+            else load_frags(raw[s & 1], snxt, s + 2 - NSUB);
+            if (s != NSUB - 2) {
+                unpack(raw[(s + 1) & 1], unp[(s + 1) & 1]);
+                mfma_all(unp[s & 1]);
+                interleave(true);
+            } else {
+                // the region after the barrier also refills stage cur with K step kt + NSTAGE, one DMA
+                // instruction after each part of the matrix work
+                const int ktn = min(kt + NSTAGE, KT - 1);
 #pragma unroll
-                    for (int c = 0; c < NPART; ++c) {
-                        unpack_part(raw[(s + 1) & 1], unp[(s + 1) & 1], c);
-                        mfma_part(unp[s & 1], c);
-                        if (c == 0) __builtin_amdgcn_sched_group_barrier(0x100, FM + FN, 0);
-                        constexpr int MPP = (NMFMA + NPART - 1) / NPART;       // most matrix instructions of a part
+                for (int c = 0; c < NPART; ++c) {
+                    unpack_part(raw[(s + 1) & 1], unp[(s + 1) & 1], c);
+                    mfma_part(unp[s & 1], c);
+                    if (c == 0) __builtin_amdgcn_sched_group_barrier(0x100, FM + FN, 0);
+                    constexpr int MPP = (NMFMA + NPART - 1) / NPART;       // most matrix instructions of a part
 #pragma unroll
-                        for (int m = 0; m < MPP; ++m) {
-                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                            __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                        issue_slot(cur, ktn, c, whole);
-                        __builtin_amdgcn_sched_barrier(0);
+                    for (int m = 0; m < MPP; ++m) {
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                        __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
                     }
+                    __builtin_amdgcn_sched_barrier(0);
+                    issue_slot(cs, ktn, c, whole);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            cur = nxt;
+        }
+    };
+    // K steps [k0, k1) starting in stage `cur`
+    auto k_steps = [&](int k0, int k1, auto whole) {
+        for (int kt = k0; kt < k1; ++kt) {
+            k_step(kt, cur, whole);
+            cur = (cur == NSTAGE - 1) ? 0 : cur + 1;
         }
     };
     // The steps that fetch the shortened last K step (a lane predicate, hence control flow between the
     // matrix instructions) are kept apart from the bulk, whose DMA is unconditional.
     const int k_whole = (tail_chunks == CPR) ? KT - 1 : max(0, KT - 1 - NSTAGE);
-    k_steps(0, k_whole, std::true_type{});
+    // the bulk in rounds of NSTAGE steps, so that each step's stage is a compile-time constant
+    int kt0 = 0;
+    for (; kt0 + NSTAGE <= k_whole; kt0 += NSTAGE)
+        static_for<NSTAGE>([&](auto c) { k_step(kt0 + c, c, std::true_type{}); });
+    k_steps(kt0, k_whole, std::true_type{});
     k_steps(k_whole, KT - 1, std::false_type{});
     {
         const unsigned char* scur = smem + cur * STAGE;
