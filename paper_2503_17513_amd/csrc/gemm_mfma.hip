@@ -156,16 +156,24 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     const int tail_chunks = (kb - (KT - 1) * RB) / 16;          // chunks of the last K step
     const int tail_sub = tail_chunks / 2;                       // its sub-steps (64 codes = 2 chunks each)
     // whole: the K step is a full one, every lane takes part (no predicate, hence no control flow)
-    auto issue_slot = [&](int stage, int kt, int s, auto whole) {
+    // Where the blocks divide evenly among the waves, a wave's first A_SLOTS slots read tokens and the others
+    // channels, whatever the wave: the operand of a slot is then known at compile time and the two bases of a K
+    // step (kbase) are computed once per step on the scalar unit instead of once per DMA.
+    constexpr bool SLOTS_STATIC = (BLKS % NW == 0) && ((BM / RPB) % NW == 0);
+    constexpr int A_SLOTS = (BM / RPB) / NW;
+    struct KBase { const uint8_t* a; const uint8_t* b; };
+    auto kbase = [&](int kt) { return KBase{qx + (int64_t)kt * RB, qw + (int64_t)kt * RB}; };
+    auto issue_slot = [&](int stage, const KBase& kbs, int s, auto whole) {
         const int blk = (wave + NW * s) % BLKS;
-        const uint8_t* base = (blk < BM / RPB ? qx : qw) + (int64_t)kt * RB;
+        const uint8_t* base = (SLOTS_STATIC ? s < A_SLOTS : blk < BM / RPB) ? kbs.a : kbs.b;
         if (decltype(whole)::value || kcl[s] < tail_chunks) dma16(base, voff[s], lds0 + stage * STAGE + blk * 1024);
     };
     auto issue = [&](int stage, int kt) {
+        const KBase kbs = kbase(kt);
 #pragma unroll
         for (int s = 0; s < CH; ++s) {
-            if (kt == KT - 1) issue_slot(stage, kt, s, std::false_type{});
-            else issue_slot(stage, kt, s, std::true_type{});
+            if (kt == KT - 1) issue_slot(stage, kbs, s, std::false_type{});
+            else issue_slot(stage, kbs, s, std::true_type{});
         }
     };
 
@@ -315,7 +323,7 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             } else {
                 // the region after the barrier also refills stage cur with K step kt + NSTAGE, one DMA
                 // instruction after each part of the matrix work
-                const int ktn = min(kt + NSTAGE, KT - 1);
+                const KBase kbs = kbase(min(kt + NSTAGE, KT - 1));
 #pragma unroll
                 for (int c = 0; c < NPART; ++c) {
                     unpack_part(raw[(s + 1) & 1], unp[(s + 1) & 1], c);
@@ -328,7 +336,7 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
                         __builtin_amdgcn_sched_group_barrier(0x002, VPM, 0);
                     }
                     __builtin_amdgcn_sched_barrier(0);
-                    issue_slot(cs, ktn, c, whole);
+                    issue_slot(cs, kbs, c, whole);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
