@@ -72,8 +72,11 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 // the second half), so that a compute unit's four waves hold tiles twice as large -- half the fragment reads
 // and unpack arithmetic per matrix instruction -- where the output only gives each compute unit a small tile;
 // the two partial accumulators are added through LDS before the epilogue.
-template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE, int MODE, int KS = 1>
-__global__ void __launch_bounds__(64 * WGM * WGN * KS)
+// LOADER: one more wave per workgroup does nothing but the DMA (all blocks of every stage) and the waits on it; the
+// others never issue a DMA.  Issuing a global_load_lds holds a wave up for tens of cycles, during which it starts
+// no matrix instruction; a wave of its own takes that off the waves that feed the matrix pipe.
+template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE, int MODE, int KS = 1, bool LOADER = false>
+__global__ void __launch_bounds__(64 * (WGM * WGN * KS + (LOADER ? 1 : 0)))
 k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             const float* __restrict__ sx, const float* __restrict__ sw,
             const int32_t* __restrict__ zx, const int32_t* __restrict__ wsum,
@@ -107,6 +110,56 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     int tm, tn;
     xcd_tile((int)blockIdx.x, tiles_m, tiles_n, xcd_gm, tm, tn);     // compact tile block per XCD
     const int m0 = tm * BM, n0 = tn * BN;
+
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(PME_AS3 unsigned char*)smem;
+    // K steps: whole steps of RB bytes, the last one possibly half as long (kb is a multiple of 64): its DMA
+    // leaves out the chunks beyond the row end and its sub-steps beyond TAIL_SUB are not computed.
+    const int KT = (kb + RB - 1) / RB;
+    const int tail_chunks = (kb - (KT - 1) * RB) / 16;          // chunks of the last K step
+    const int tail_sub = tail_chunks / 2;                       // its sub-steps (64 codes = 2 chunks each)
+
+    if constexpr (LOADER) {
+        if (wave == NW) {
+            // The loader wave.  It meets the other waves at the same barriers as they meet each other (one before
+            // the K loop, one per K step, one after the loop) and leaves after the last of them; later barriers
+            // count the waves still running.
+            // swz(row) only looks at row bits below RPB's, so a lane moves the same chunk of its row in every block.
+            static_assert(RPB % (RB == 64 ? 16 : 8) == 0, "the swizzle must not depend on the block");
+            constexpr int FIRST_WAIT = (NSTAGE - 1) * BLKS < 63 ? (NSTAGE - 1) * BLKS : 63;   // vmcnt has 6 bits
+            static_assert((NSTAGE - 2) * BLKS <= 63, "the wait count of the K loop must fit vmcnt");
+            const int lr = lane / CPR, kc = (lane % CPR) ^ swz<RB>(lr);
+            uint32_t off[BLKS];
+#pragma unroll
+            for (int blk = 0; blk < BLKS; ++blk) {
+                const int r = RPB * blk + lr;
+                const int row = (r < BM) ? min(m0 + r, T - 1) : min(n0 + r - BM, N - 1);
+                off[blk] = (uint32_t)row * (uint32_t)kb + (uint32_t)(kc * 16);
+            }
+            auto issue_stage = [&](int stage, int kt) {
+                const uint8_t* pa = qx + (int64_t)kt * RB;
+                const uint8_t* pb = qw + (int64_t)kt * RB;
+                if (kt < KT - 1 || kc < tail_chunks) {          // the shortened last K step: lanes beyond the row end idle
+#pragma unroll
+                    for (int blk = 0; blk < BLKS; ++blk)
+                        dma16(blk < BM / RPB ? pa : pb, off[blk], lds0 + stage * STAGE + blk * 1024);
+                }
+            };
+#pragma unroll
+            for (int st = 0; st < NSTAGE; ++st) issue_stage(st, min(st, KT - 1));
+            wait_vm<FIRST_WAIT>();
+            lds_barrier();
+            int cur = 0;
+            for (int kt = 0; kt + 1 < KT; ++kt) {
+                wait_vm<(NSTAGE - 2) * BLKS>();
+                lds_barrier();          // K step kt + 1 has landed; every wave has left the stage of K step kt
+                issue_stage(cur, min(kt + NSTAGE, KT - 1));
+                cur = (cur == NSTAGE - 1) ? 0 : cur + 1;
+            }
+            wait_vm<0>();
+            lds_barrier();
+            return;
+        }
+    }
 
     // DMA source of each 16-byte chunk this lane moves: block blk covers tile rows RPB blk .. RPB blk + RPB - 1;
     // lane L writes chunk position L % CPR of row RPB blk + L / CPR, which holds chunk (L % CPR) ^ swz(row).
@@ -149,12 +202,6 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             else if (idx < ROWS) prez[q] = wsum[min(n0 + idx - BM, N - 1)];
         }
     }
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(PME_AS3 unsigned char*)smem;
-    // K steps: whole steps of RB bytes, the last one possibly half as long (kb is a multiple of 64): its DMA
-    // leaves out the chunks beyond the row end and its sub-steps beyond TAIL_SUB are not computed.
-    const int KT = (kb + RB - 1) / RB;
-    const int tail_chunks = (kb - (KT - 1) * RB) / 16;          // chunks of the last K step
-    const int tail_sub = tail_chunks / 2;                       // its sub-steps (64 codes = 2 chunks each)
     // whole: the K step is a full one, every lane takes part (no predicate, hence no control flow)
     // Where the blocks divide evenly among the waves, a wave's first A_SLOTS slots read tokens and the others
     // channels, whatever the wave: the operand of a slot is then known at compile time and the two bases of a K
@@ -291,9 +338,11 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     // start the DMA of K step kt + NSTAGE into that stage.  Every K step issues the same number of DMA
     // instructions (beyond the end the last step is loaded again into a stage nobody reads), so the
     // wait count is a constant: the NSTAGE - 2 newest groups may still be in flight.
+    if constexpr (!LOADER) {
 #pragma unroll
-    for (int st = 0; st < NSTAGE; ++st) issue(st, min(st, KT - 1));
-    wait_vm<(NSTAGE - 1) * CH>();
+        for (int st = 0; st < NSTAGE; ++st) issue(st, min(st, KT - 1));
+        wait_vm<(NSTAGE - 1) * CH>();
+    }
     lds_barrier();
     Frags raw[2];
     Unpacked unp[2];
@@ -311,12 +360,12 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
 #pragma unroll
         for (int s = 0; s < NSUB; ++s) {
             if (s == NSUB - 2) {
-                wait_vm<(NSTAGE - 2) * CH>();
+                if constexpr (!LOADER) wait_vm<(NSTAGE - 2) * CH>();
                 lds_barrier();      // stage nxt has landed for every wave; every wave has left stage cur
             }
             if (s + 2 < NSUB) load_frags(raw[s & 1], scur, s + 2);
             else load_frags(raw[s & 1], snxt, s + 2 - NSUB);
-            if (s != NSUB - 2) {
+            if (LOADER || s != NSUB - 2) {
                 unpack(raw[(s + 1) & 1], unp[(s + 1) & 1]);
                 mfma_all(unp[s & 1]);
                 interleave(true);
@@ -369,7 +418,7 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             }
         }
     }
-    wait_vm<0>();
+    if constexpr (!LOADER) wait_vm<0>();
     lds_barrier();
 
     // ---- K split: wave kh finishes the token blocks i of half kh; it hands the other half's partial sums to
@@ -500,25 +549,25 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     else epilogue(std::integral_constant<int, KS - 1>{});
 }
 
-template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE, int KS = 1>
+template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE, int KS = 1, bool LOADER = false>
 pme_status launch_tile(const GemmArgs& a) {
     const int kb = (int)(a.d_e / 2);
     if (kb % 64) return PME_ERR_UNSUPPORTED_PATH;      // whole sub-steps; the last K step may be half as long
     if ((int64_t)std::max(a.T, a.N) * kb >= (int64_t(1) << 32)) return PME_ERR_UNSUPPORTED_PATH;   // 32-bit DMA offsets
     const int tiles_m = (int)((a.T + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WGM * WGN * KS);
+    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * (WGM * WGN * KS + (LOADER ? 1 : 0)));
     const size_t lds = (size_t)NSTAGE * (BM + BN) * RB;
     if (lds > 64 * 1024) {
         static std::atomic<uint32_t> done[3];
-        if (allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_BF16, KS>, (int)lds, done[0]) != PME_OK ||
-            allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_ASYM, KS>, (int)lds, done[1]) != PME_OK ||
-            allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_I32, KS>, (int)lds, done[2]) != PME_OK)
+        if (allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_BF16, KS, LOADER>, (int)lds, done[0]) != PME_OK ||
+            allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_ASYM, KS, LOADER>, (int)lds, done[1]) != PME_OK ||
+            allow_dynamic_lds(k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE_I32, KS, LOADER>, (int)lds, done[2]) != PME_OK)
             return PME_ERR_HIP;
     }
     // 16-byte output pieces need 8-element alignment of N, the pitch and the base
     const int vec = (a.N % 8 == 0 && a.ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0) ? 1 : 0;
 #define PME_LAUNCH(MODE)                                                                                        \
-    hipLaunchKernelGGL((k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE, KS>), grid, block, lds, a.stream, a.qx, a.qw, \
+    hipLaunchKernelGGL((k_gemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, MODE, KS, LOADER>), grid, block, lds, a.stream, a.qx, a.qw, \
                        a.sx, a.sw, a.zx, a.wsum, (int)a.T, (int)a.N, kb, a.y, a.ldy, tiles_m, tiles_n, xcd_grid_m(tiles_m, tiles_n, BM, BN), vec)
     if (a.out_i32) PME_LAUNCH(MODE_I32);
     else if (a.zx) PME_LAUNCH(MODE_ASYM);
@@ -547,12 +596,12 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
         // (a half-length last step is supported but measured no faster than 64-byte steps, so those are kept
         // when d_e is not a multiple of 256)
         const bool wide = (a.d_e % 256) == 0;
-        // (with 64-byte steps 128 x 192 on 4 waves beats 128 x 256 on 8 by a quarter; where the output only
-        // gives a compute unit 128 x 128, splitting K between wave pairs gains 3-10 % over 64 x 64 wave tiles)
+        // (with 64-byte steps 128 x 192 on 4 waves beats 128 x 256 on 8 by a quarter; a fifth wave that does the
+        // DMA gains another 3-4 % there, and 1-2 % at 128 x 128 over splitting K between wave pairs)
         if (tiles(256, 256) >= cus) id = wide ? 11 : 8;
         else if (wide && tiles(128, 256) >= cus) id = 16;
-        else if (tiles(128, 192) >= cus) id = wide ? 15 : 9;
-        else if (tiles(128, 128) >= cus) id = wide ? 19 : 4;
+        else if (tiles(128, 192) >= cus) id = wide ? 15 : 21;
+        else if (tiles(128, 128) >= cus) id = 22;
         else if (tiles(64, 128) >= cus / 2) id = 6;
         else id = 7;
     }
@@ -579,6 +628,9 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
         // two waves per wave tile, each taking half of every K step
         case 19: return launch_tile<128, 128, 1, 2, 128, 3, 2>(a); // 2 x 2 waves of 128 x 64
         case 20: return launch_tile<128, 192, 1, 2, 128, 3, 2>(a); // 2 x 2 waves of 128 x 96
+        // a fifth wave issues all the DMA
+        case 21: return launch_tile<128, 192, 2, 2, 64, 3, 1, true>(a);    // 4 waves of 64 x 96 + loader
+        case 22: return launch_tile<128, 128, 2, 2, 64, 3, 1, true>(a);    // 4 waves of 64 x 64 + loader
     }
     return PME_ERR_UNSUPPORTED_PATH;
 }
