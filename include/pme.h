@@ -196,7 +196,10 @@ pme_status pme_probe_copy(const void* src, void* dst, size_t bytes, void* stream
 
 /* Back-to-back independent matrix-core instructions, nothing else in the loop: the measured ceiling the
  * GEMMs are priced against next to the published peak.  kind 0: v_mfma_i32_32x32x32_i8 (the int4 path's
- * instruction), kind 1: v_mfma_scale_f32_32x32x64_f8f6f4 on FP4 operands (the MXFP4 path's).  Launches 512
+ * instruction), kind 1: v_mfma_scale_f32_32x32x64_f8f6f4 on FP4 operands (the MXFP4 path's), both on near-constant
+ * operands; kinds 2 and 3: the same two instructions on pseudo-random codes (for int8 the bytes the int4 GEMM
+ * feeds the pipe: a random nibble times 16), whose rate is lower because the pipe is power-limited (iters is
+ * rounded up to a multiple of 4 for these two).  Launches 512
  * workgroups of 256 threads, each wave issuing 4 * iters instructions; out: DEVICE int32, at least
  * 512 * 256 elements (a checksum that keeps the loop alive); *ops (HOST, may be null) receives the operation
  * count of one launch (2 per multiply-add).  PME_ERR_DTYPE for another kind, PME_ERR_SHAPE for a short

@@ -307,7 +307,8 @@ def probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
 
 
 def probe_mfma(kind: int, out: torch.Tensor, iters: int) -> float:
-    """Launch the matrix-core probe (kind 0 int8, 1 FP4) and return the operation count of the launch."""
+    """Launch the matrix-core probe (kind 0 int8, 1 FP4; 2, 3 the same on pseudo-random codes) and return the
+    operation count of the launch."""
     ops = C.c_double(0.0)
     _check(lib().pme_probe_mfma(int(kind), _dev(out, "out"), out.numel(), int(iters), C.byref(ops), _stream()),
            "pme_probe_mfma")

@@ -365,10 +365,11 @@ pme_status pme_probe_copy(const void* src, void* dst, size_t bytes, void* stream
 
 pme_status pme_probe_mfma(int kind, int32_t* out, size_t out_elems, int iters, double* ops, void* stream) {
     if (!out) return PME_ERR_NULL;
-    if (kind != 0 && kind != 1) return PME_ERR_DTYPE;
+    if (kind < 0 || kind > 3) return PME_ERR_DTYPE;
     if (iters < 0 || iters > (1 << 24) || out_elems < (size_t)pme::kProbeMfmaBlocks * 256) return PME_ERR_SHAPE;
     if (!aligned(out, 4)) return PME_ERR_ALIGN;
-    if (ops) *ops = (double)pme::kProbeMfmaBlocks * 4 * 4 * (double)iters * (kind == 0 ? 65536.0 : 131072.0);
+    if (kind >= 2) iters = (iters + 3) / 4 * 4;           // the random-code loops run in rounds of four iterations
+    if (ops) *ops = (double)pme::kProbeMfmaBlocks * 4 * 4 * (double)iters * ((kind & 1) == 0 ? 65536.0 : 131072.0);
     return pme::launch_probe_mfma(kind, out, iters, (hipStream_t)stream);
 }
 

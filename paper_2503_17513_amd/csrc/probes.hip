@@ -3,6 +3,8 @@
 //   k_probe_copy  plain streaming copy (HBM read + write).
 //   k_probe_mfma  back-to-back independent matrix-core instructions with nothing else in the loop:
 //                 the rate the matrix pipe sustains at the clock the chip actually holds under that load.
+//                 That rate depends on the operands' bit activity (the pipe is power-limited), so the probe runs
+//                 on near-constant operands (which reach the published peak) and on pseudo-random codes.
 #include "pme_internal.h"
 
 namespace pme {
@@ -20,14 +22,65 @@ k_probe_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16)
     for (; i < n16; i += stride) dst[i] = src[i];
 }
 
+__device__ __forceinline__ uint32_t probe_rand(uint32_t& state) {
+    state = state * 1664525u + 1013904223u;         // a linear congruential step; the high half is the usable part
+    return state;
+}
+
 // Four independent accumulator chains per wave, so that the pipe never waits on a result.
 // KIND 0: v_mfma_i32_32x32x32_i8 (65536 ops each).  KIND 1: v_mfma_scale_f32_32x32x64_f8f6f4 with FP4
 // operands (131072 flops each).  The operands are small integers / small E2M1 codes; sums stay finite.
+// KIND 2 / 3: the same two instructions on pseudo-random codes -- for int8 the bytes the int4 GEMM feeds the
+// pipe (a random nibble times 16), for FP4 random E2M1 codes -- over four operand register sets that rotate
+// against the accumulators, so that consecutive instructions toggle the operand buses as a GEMM does.
 template <int KIND>
 __global__ void __launch_bounds__(256) k_probe_mfma(int32_t* __restrict__ out, int iters) {
     const int t = (int)threadIdx.x;
     int32_t s = 0;
-    if constexpr (KIND == 0) {
+    if constexpr (KIND == 2 || KIND == 3) {
+        uint32_t state = 12345u + (uint32_t)t * 7919u + blockIdx.x * 104729u;
+        i32x8 a[4], b[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                uint32_t ra = (probe_rand(state) >> 16) | (probe_rand(state) & 0xFFFF0000u);
+                uint32_t rb = (probe_rand(state) >> 16) | (probe_rand(state) & 0xFFFF0000u);
+                if (KIND == 2) { ra &= 0xF0F0F0F0u; rb &= 0xF0F0F0F0u; }
+                a[q][e] = e < 4 ? (int)ra : 0;
+                b[q][e] = e < 4 ? (int)rb : 0;
+            }
+        if constexpr (KIND == 2) {
+            i32x16 c[4] = {{0}, {0}, {0}, {0}};
+            // rounds of 16 instructions with compile-time register numbers (iters is rounded up to a multiple of 4)
+            for (int it = 0; it < iters; it += 4) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const i32x8& ar = a[(q + r) & 3];
+                        const i32x4 aq = {ar[0], ar[1], ar[2], ar[3]};
+                        const i32x4 bq = {b[q][0], b[q][1], b[q][2], b[q][3]};
+                        c[q] = __builtin_amdgcn_mfma_i32_32x32x32_i8(aq, bq, c[q], 0, 0, 0);
+                    }
+            }
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s += c[0][e] + c[1][e] + c[2][e] + c[3][e];
+        } else {
+            f32x16 c[4] = {{0}, {0}, {0}, {0}};
+            for (int it = 0; it < iters; it += 4) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+#pragma unroll
+                    for (int q = 0; q < 4; ++q)
+                        c[q] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a[(q + r) & 3], b[q], c[q], 4, 4, 0, 120, 0, 120);
+            }
+            float f = 0.f;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) f += c[0][e] + c[1][e] + c[2][e] + c[3][e];
+            s = (int32_t)__float_as_uint(f);
+        }
+    } else if constexpr (KIND == 0) {
         const i32x4 a = {0x01010101 * (t & 3), 0x01000100, 0x00010001, 0x01010101};
         const i32x4 b = {0x01010101, 0x00010001, 0x01000100, 0x01010101 * ((t >> 2) & 1)};
         i32x16 c0 = {0}, c1 = {0}, c2 = {0}, c3 = {0};
@@ -71,7 +124,9 @@ pme_status launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream
 pme_status launch_probe_mfma(int kind, int32_t* out, int iters, hipStream_t s) {
     // 512 workgroups of 4 waves: two waves on every SIMD of the 256 compute units
     if (kind == 0) hipLaunchKernelGGL(k_probe_mfma<0>, dim3(kProbeMfmaBlocks), dim3(256), 0, s, out, iters);
-    else hipLaunchKernelGGL(k_probe_mfma<1>, dim3(kProbeMfmaBlocks), dim3(256), 0, s, out, iters);
+    else if (kind == 1) hipLaunchKernelGGL(k_probe_mfma<1>, dim3(kProbeMfmaBlocks), dim3(256), 0, s, out, iters);
+    else if (kind == 2) hipLaunchKernelGGL(k_probe_mfma<2>, dim3(kProbeMfmaBlocks), dim3(256), 0, s, out, iters);
+    else hipLaunchKernelGGL(k_probe_mfma<3>, dim3(kProbeMfmaBlocks), dim3(256), 0, s, out, iters);
     return hip_status(hipGetLastError());
 }
 

@@ -183,7 +183,8 @@ def test_probe_mfma_errors():
     f = pme.lib().pme_probe_mfma
     n = 512 * 256
     assert f(0, None, n, 10, None, None) == NULL
-    assert f(2, FAKE, n, 10, None, None) == DTYPE
+    assert f(4, FAKE, n, 10, None, None) == DTYPE
+    assert f(-1, FAKE, n, 10, None, None) == DTYPE
     assert f(0, FAKE, n - 1, 10, None, None) == SHAPE
     assert f(1, FAKE, n, -1, None, None) == SHAPE
     assert f(0, FAKE + 2, n, 10, None, None) == ALIGN

@@ -532,6 +532,17 @@ def test_probe_mfma():
     assert f10.abs().sum().item() > 0 and torch.equal(out.view(torch.float32), 2 * f10)
 
 
+def test_probe_mfma_on_random_codes():
+    out = torch.zeros(512 * 256, dtype=torch.int32, device="cuda")
+    assert pme.probe_mfma(2, out, 8) == 512 * 16 * 8 * 65536.0
+    # the operand sets rotate with a period of four iterations: equal runs of 8 iterations add equal sums
+    one = out.clone()
+    pme.probe_mfma(2, out, 24)
+    assert one.abs().sum().item() > 0 and torch.equal(out, 3 * one)
+    assert pme.probe_mfma(3, out, 8) == 512 * 16 * 8 * 131072.0
+    assert torch.isfinite(out.view(torch.float32)).all()
+
+
 def test_probe_copy():
     src = torch.arange(1 << 20, dtype=torch.int32, device="cuda")
     dst = torch.zeros_like(src)
