@@ -60,6 +60,7 @@ ROTATE_CASES = [
     ("b20_k9", 3, 8192, 10240, "bf16", (GENERIC, MFMA)),
     ("b12_k10", 2, 8192, 12288, "bf16", (GENERIC, MFMA)),
     ("single_token", 1, 2048, 2176, "bf16", (GENERIC, MFMA)),
+    ("b140_k6_three_tiles_per_wave", 3080, 8192, 8960, "bf16", (MFMA,)),          # the launch for 3072 tokens and more
     # 1024 tokens or more at 2^k = 32: workgroups whose waves each rotate tokens of their own (token counts
     # that do not divide by the waves of a workgroup, one- and five-tile blocks, ragged d)
     ("b68_k5_token_per_wave", 1030, 2048, 2176, "bf16", (MFMA,)),
