@@ -11,6 +11,7 @@
 //    to another; the per-step barrier waits for LDS traffic only and for all but the newest
 //    stage's DMA (vmcnt counts in order).  The DMA instructions of a K step are spread between the
 //    matrix instructions of the region after the barrier (issuing one holds the wave up).
+//    In the variants with a loader wave, a fifth wave issues every DMA and the four matrix waves none.
 //  * LDS -> registers: one ds_read_b128 per lane brings 32 codes, unpacked in registers into two
 //    int8 MFMA operands:   even codes (w & 0x0F0F0F0F) << 4,   odd codes w & 0xF0F0F0F0.
 //    A nibble moved to the top of a byte is 16 x its two's-complement value: no sign extension.
