@@ -602,9 +602,11 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
         if (tiles(256, 256) >= cus) id = wide ? 11 : 8;
         else if (wide && tiles(128, 256) >= cus) id = 16;
         else if (tiles(128, 192) >= cus) id = wide ? 15 : 21;
-        else if (tiles(128, 128) >= cus) id = 22;
-        else if (tiles(64, 128) >= cus / 2) id = 6;
-        else id = 7;
+        // smaller outputs (measured on 18 shapes from 96 to 1536 tokens): 128 x 128 from three quarters of the
+        // compute units on, else 64 x 64, which beats 64 x 128 until the latter has one and a half tiles per unit
+        else if (tiles(128, 128) >= cus * 3 / 4) id = 22;
+        else if (tiles(64, 128) >= cus * 3 / 2) id = 23;
+        else id = 24;
     }
     switch (id) {
         case 1: return launch_tile<256, 256, 2, 4, 64, 3>(a);      // 8 waves of 128 x 64
@@ -632,6 +634,8 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
         // a fifth wave issues all the DMA
         case 21: return launch_tile<128, 192, 2, 2, 64, 3, 1, true>(a);    // 4 waves of 64 x 96 + loader
         case 22: return launch_tile<128, 128, 2, 2, 64, 3, 1, true>(a);    // 4 waves of 64 x 64 + loader
+        case 23: return launch_tile<64, 128, 2, 2, 64, 3, 1, true>(a);     // 4 waves of 32 x 64 + loader
+        case 24: return launch_tile<64, 64, 2, 2, 64, 3, 1, true>(a);      // 4 waves of 32 x 32 + loader
     }
     return PME_ERR_UNSUPPORTED_PATH;
 }
