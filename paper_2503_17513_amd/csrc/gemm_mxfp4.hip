@@ -45,8 +45,10 @@ __device__ __forceinline__ uint32_t pack_bf16(float a, float b) {
 }
 
 // BM x BN output tile, WGM x WGN waves, RB packed bytes (2 RB codes, RB / 16 scale bytes) per row and K step.
-template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE>
-__global__ void __launch_bounds__(64 * WGM * WGN)
+// LOADER: one more wave per workgroup issues every DMA (codes and scale bytes of every stage) and waits for them;
+// the matrix waves issue none (as in the int4 kernel: issuing a DMA holds a wave up for tens of cycles).
+template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE, bool LOADER = false>
+__global__ void __launch_bounds__(64 * (WGM * WGN + (LOADER ? 1 : 0)))
 k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, const uint8_t* __restrict__ qw,
               const uint8_t* __restrict__ ew, int T, int N, int kb, int eb, uint16_t* __restrict__ y, int64_t ldo,
               int tiles_m, int tiles_n, int xcd_gm, int vec_store) {
@@ -73,6 +75,59 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
     xcd_tile((int)blockIdx.x, tiles_m, tiles_n, xcd_gm, tm, tn);     // compact tile block per XCD
     const int m0 = tm * BM, n0 = tn * BN;
 
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(PME_AS3 unsigned char*)smem;
+    const int KT = kb / RB;
+    if constexpr (LOADER) {
+        if (wave == NW) {
+            // The loader wave meets the matrix waves at their barriers (one before the K loop, one per K step, one
+            // after the loop) and leaves after the last; later barriers count the waves still running.
+            static_assert(RPB % (RB == 64 ? 16 : 8) == 0, "the swizzle must not depend on the block");
+            constexpr int PER_STAGE = BLKS + SBLKS;
+            constexpr int FIRST_WAIT = (NSTAGE - 1) * PER_STAGE < 63 ? (NSTAGE - 1) * PER_STAGE : 63;   // vmcnt has 6 bits
+            static_assert((NSTAGE - 2) * PER_STAGE <= 63, "the wait count of the K loop must fit vmcnt");
+            const int lr = lane / CPR, kc = (lane % CPR) ^ swz<RB>(lr);
+            uint32_t off[BLKS], soff[SBLKS];
+#pragma unroll
+            for (int blk = 0; blk < BLKS; ++blk) {
+                const int r = RPB * blk + lr;
+                const int row = (r < BM) ? min(m0 + r, T - 1) : min(n0 + r - BM, N - 1);
+                off[blk] = (uint32_t)row * (uint32_t)kb + (uint32_t)(kc * 16);
+            }
+#pragma unroll
+            for (int sb = 0; sb < SBLKS; ++sb) {
+                const int plane = sb / (ROWS / 64), r = 64 * (sb % (ROWS / 64)) + lane;
+                const int row = (r < BM) ? min(m0 + r, T - 1) : min(n0 + r - BM, N - 1);
+                soff[sb] = (uint32_t)row * (uint32_t)eb + (uint32_t)(4 * plane);
+            }
+            auto issue_stage = [&](int stage, int kt) {
+                const uint8_t* pa = qx + (int64_t)kt * RB;
+                const uint8_t* pb = qw + (int64_t)kt * RB;
+                const uint8_t* sa = ex + (int64_t)kt * (RB / 16);
+                const uint8_t* sb_ = ew + (int64_t)kt * (RB / 16);
+#pragma unroll
+                for (int blk = 0; blk < BLKS; ++blk)
+                    dma16(blk < BM / RPB ? pa : pb, off[blk], lds0 + stage * STAGE + blk * 1024);
+#pragma unroll
+                for (int sb = 0; sb < SBLKS; ++sb)
+                    dma4(64 * (sb % (ROWS / 64)) < BM ? sa : sb_, soff[sb], lds0 + stage * STAGE + CODE_BYTES + sb * 256);
+            };
+#pragma unroll
+            for (int st = 0; st < NSTAGE; ++st) issue_stage(st, min(st, KT - 1));
+            wait_vm<FIRST_WAIT>();
+            lds_barrier();
+            int cur = 0;
+            for (int kt = 0; kt + 1 < KT; ++kt) {
+                wait_vm<(NSTAGE - 2) * PER_STAGE>();
+                lds_barrier();          // K step kt + 1 has landed; every wave has left the stage of K step kt
+                issue_stage(cur, min(kt + NSTAGE, KT - 1));
+                cur = (cur == NSTAGE - 1) ? 0 : cur + 1;
+            }
+            wait_vm<0>();
+            lds_barrier();
+            return;
+        }
+    }
+
     // A DMA block lies wholly in the token rows or wholly in the channel rows, so the operand a slot reads
     // from is wave-uniform; the lane keeps its byte offset within that operand.
     static_assert(BM % RPB == 0 && BM % 64 == 0, "DMA blocks do not straddle the operands");
@@ -93,7 +148,6 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
         const int row = (r < BM) ? min(m0 + r, T - 1) : min(n0 + r - BM, N - 1);
         svoff[s] = (uint32_t)row * (uint32_t)eb + (uint32_t)(4 * plane);
     }
-    const uint32_t lds0 = (uint32_t)(uintptr_t)(PME_AS3 unsigned char*)smem;
     // DMA slot q of this wave for K step kt: slots 0 .. CH - 1 move codes, CH .. CH + SCH - 1 scale bytes
     constexpr int NSLOT = CH + SCH;
     auto issue_slot = [&](int stage, int kt, int q) {
@@ -177,10 +231,11 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
     // Pipeline over sub-steps g = kt NSUB + s: read the fragments of g + 1 while the matrix cores work on g.
     // Before the region whose read first touches K step kt + 1 (s = NSUB - 1) every read of K step kt has been
     // issued: wait for the DMA of kt + 1, barrier, start the DMA of kt + NSTAGE into the stage just left.
-    const int KT = kb / RB;
+    if constexpr (!LOADER) {
 #pragma unroll
-    for (int st = 0; st < NSTAGE; ++st) issue(st, min(st, KT - 1));
-    wait_vm<(NSTAGE - 1) * (CH + SCH)>();
+        for (int st = 0; st < NSTAGE; ++st) issue(st, min(st, KT - 1));
+        wait_vm<(NSTAGE - 1) * (CH + SCH)>();
+    }
     lds_barrier();
     Frags raw[2];
     load_frags(raw[0], smem, 0, raw[0]);
@@ -191,7 +246,11 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
         const unsigned char* snxt = smem + nxt * STAGE;
 #pragma unroll
         for (int s = 0; s < NSUB; ++s) {
-            if (s == NSUB - 1) {
+            if (LOADER && s == NSUB - 1) {
+                lds_barrier();
+                load_frags(raw[(s + 1) & 1], snxt, 0, raw[s & 1]);
+                mfma_all(raw[s & 1], (s & 1) != 0);
+            } else if (s == NSUB - 1) {
                 wait_vm<(NSTAGE - 2) * (CH + SCH)>();
                 lds_barrier();
                 load_frags(raw[(s + 1) & 1], snxt, 0, raw[s & 1]);
@@ -226,7 +285,7 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
             mfma_all(raw[s & 1], (s & 1) != 0);
         }
     }
-    wait_vm<0>();
+    if constexpr (!LOADER) wait_vm<0>();
     lds_barrier();
 
     // ---- epilogue.  Accumulator element e of block (i, j): output channel n0 + wn WN + 32 j + 8 (e / 4) + 4 fk + e % 4,
@@ -264,15 +323,15 @@ k_mxgemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, co
     }
 }
 
-template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE>
+template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE, bool LOADER = false>
 pme_status launch_tile(const MxGemmArgs& a) {
     const int kb = (int)(a.d_e / 2), eb = (int)(a.d_e / 32);
     if (kb % RB) return PME_ERR_UNSUPPORTED_PATH;
     if ((int64_t)std::max(a.T, a.N) * kb >= (int64_t(1) << 32)) return PME_ERR_UNSUPPORTED_PATH;   // 32-bit DMA offsets
     const int tiles_m = (int)((a.T + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
-    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * WGM * WGN);
+    const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * (WGM * WGN + (LOADER ? 1 : 0)));
     const size_t lds = (size_t)NSTAGE * ((BM + BN) * RB + (BM + BN) * 4 * (RB / 64));
-    auto kern = k_mxgemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE>;
+    auto kern = k_mxgemm_mfma<BM, BN, WGM, WGN, RB, NSTAGE, LOADER>;
     static std::atomic<uint32_t> done;
     if (lds > 64 * 1024 && allow_dynamic_lds(kern, (int)lds, done) != PME_OK) return PME_ERR_HIP;
     const int vec = (a.N % 8 == 0 && a.ldy % 8 == 0 && (reinterpret_cast<uintptr_t>(a.y) & 15) == 0) ? 1 : 0;
@@ -451,9 +510,9 @@ pme_status launch_mxgemm_mfma(const MxGemmArgs& a) {
         // from a sweep of every tile over 9 shapes
         if (tiles(256, 256) >= cus) id = wide ? 8 : 2;
         else if (wide && tiles(256, 128) >= cus) id = 9;
-        else if (tiles(128, 192) >= cus && (!wide || tiles(128, 256) < cus)) id = wide ? 6 : 5;
+        else if (tiles(128, 192) >= cus && (!wide || tiles(128, 256) < cus)) id = wide ? 6 : 10;
         else if (tiles(128, 128) >= cus / 2) id = wide ? 3 : 4;
-        else id = 7;
+        else id = 11;
     }
     switch (id) {
         case 1: return launch_tile<256, 256, 2, 2, 128, 2>(a);
@@ -465,6 +524,10 @@ pme_status launch_mxgemm_mfma(const MxGemmArgs& a) {
         case 7: return launch_tile<64, 64, 2, 2, 64, 3>(a);
         case 8: return launch_tile<256, 256, 2, 4, 128, 2>(a);
         case 9: return launch_tile<256, 128, 2, 2, 128, 3>(a);
+        // a fifth wave issues all the DMA (pays with 64-byte rows: 128 x 192 -4 %, 64 x 64 up to -14 %; with 128-byte rows
+        // at 128 x 128 one wave cannot issue a stage's 40 DMA instructions in the time of its 16 matrix instructions per wave)
+        case 10: return launch_tile<128, 192, 2, 2, 64, 3, true>(a);
+        case 11: return launch_tile<64, 64, 2, 2, 64, 3, true>(a);
     }
     return PME_ERR_UNSUPPORTED_PATH;
 }

@@ -125,7 +125,7 @@ def test_mxfp4_gemm(name, T, N, d_e, paths):
         check_mx_gemm(y, qx, ex, qw, ew)
 
 
-@pytest.mark.parametrize("tile", range(1, 10))
+@pytest.mark.parametrize("tile", range(1, 12))
 def test_mxfp4_gemm_every_tile(tile):
     rng = np.random.default_rng(tile)
     T, N, d_e = 300, 520, 1280
