@@ -599,12 +599,30 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
         const bool wide = (a.d_e % 256) == 0;
         // (with 64-byte steps 128 x 192 on 4 waves beats 128 x 256 on 8 by a quarter; a fifth wave that does the
         // DMA gains another 3-4 % there, and 1-2 % at 128 x 128 over splitting K between wave pairs)
-        if (tiles(256, 256) >= cus) id = wide ? 11 : 8;
-        else if (wide && tiles(128, 256) >= cus) id = 16;
-        else if (tiles(128, 192) >= cus) id = wide ? 15 : 21;
-        // smaller outputs (measured on 18 shapes from 96 to 1536 tokens): 128 x 128 from three quarters of the
-        // compute units on, else 64 x 64, which beats 64 x 128 until the latter has one and a half tiles per unit
-        else if (tiles(128, 128) >= cus * 3 / 4) id = 22;
+        if (tiles(128, 128) >= cus * 3 / 4) {
+            // Large outputs: the cheapest of four tile shapes by rounds x tile area / efficiency.  The efficiencies
+            // are each shape's measured rate on outputs of many rounds, relative to 256 x 256; a round is one
+            // workgroup on every compute unit, except that two 128 x 192 workgroups without loader wave share a
+            // unit (a pair takes about 1.7 x one, and a unit with a second workgroup about 1.5 x).  The model
+            // ranks the shapes as 14 measured outputs from 512 x 14336 to 4096 x 4096 do.
+            auto rounds = [&](int64_t t) { return (double)((t + cus - 1) / cus); };
+            auto rounds_shared = [&](int64_t t) {
+                const int64_t pairs = (t - 1) / (2 * cus);
+                const double rest = (double)(t - 2 * cus * pairs) / (double)cus;       // (0, 2]
+                return 1.7 * (double)pairs + (rest <= 1.0 ? 1.0 : 1.5 + 0.2 * (rest - 1.0));
+            };
+            const double c256 = rounds(tiles(256, 256)) * (256.0 * 256.0) / 1.00;
+            const double c16 = wide ? rounds(tiles(128, 256)) * (128.0 * 256.0) / 0.87 : 1e30;
+            const double c192 = rounds_shared(tiles(128, 192)) * (128.0 * 192.0) / 0.83;
+            const double c128 = rounds(tiles(128, 128)) * (128.0 * 128.0) / 0.76;
+            const double best = std::min(std::min(c256, c16), std::min(c192, c128));
+            if (best == c256) id = wide ? 11 : 8;
+            else if (best == c16) id = 16;
+            else if (best == c192) id = tiles(128, 192) <= cus ? 21 : 9;     // the loader's registers allow one workgroup per unit
+            else id = 22;
+        }
+        // smaller outputs (measured on 18 shapes from 96 to 1536 tokens): 64 x 64, which beats 64 x 128 until the
+        // latter has one and a half tiles per compute unit
         else if (tiles(64, 128) >= cus * 3 / 2) id = 23;
         else id = 24;
     }
