@@ -20,7 +20,10 @@
  *  - Pointers named in the comments as DEVICE are HIP device memory owned by the
  *    caller.  The library never allocates, frees or synchronises; every call only
  *    enqueues kernels on `stream` (a hipStream_t passed as void*, NULL = default
- *    stream) and returns.
+ *    stream) and returns.  One exception: the first rotation of a new shape (d, d_e) on a device fills a
+ *    table of base-block fragments in library-owned device memory (a static pool of 16 MB per device, 7 to
+ *    154 KB per shape, kept for the life of the process) and waits for that small kernel once; run a shape
+ *    once before capturing it in a HIP graph.
  *  - Arguments are validated on the host before any HIP call.  A status other than
  *    PME_OK means nothing was launched (PME_ERR_HIP excepted: a launch was refused by
  *    the runtime).  No C++ exception crosses this boundary.
