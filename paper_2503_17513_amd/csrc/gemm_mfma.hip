@@ -612,12 +612,12 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
                 return 1.7 * (double)pairs + (rest <= 1.0 ? 1.0 : 1.5 + 0.2 * (rest - 1.0));
             };
             const double c256 = rounds(tiles(256, 256)) * (256.0 * 256.0) / 1.00;
-            const double c16 = wide ? rounds(tiles(128, 256)) * (128.0 * 256.0) / 0.87 : 1e30;
+            const double c16 = rounds(tiles(128, 256)) * (128.0 * 256.0) / 0.87;
             const double c192 = rounds_shared(tiles(128, 192)) * (128.0 * 192.0) / 0.83;
             const double c128 = rounds(tiles(128, 128)) * (128.0 * 128.0) / 0.76;
             const double best = std::min(std::min(c256, c16), std::min(c192, c128));
             if (best == c256) id = wide ? 11 : 8;
-            else if (best == c16) id = 16;
+            else if (best == c16) id = wide ? 16 : 2;
             else if (best == c192) id = tiles(128, 192) <= cus ? 21 : 9;     // the loader's registers allow one workgroup per unit
             else id = 22;
         }
