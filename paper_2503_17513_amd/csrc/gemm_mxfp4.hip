@@ -507,12 +507,30 @@ pme_status launch_mxgemm_mfma(const MxGemmArgs& a) {
     int id = g_mx_tile_override;
     if (id == 0) {
         const bool wide = (a.d_e % 256) == 0;
-        // from a sweep of every tile over 9 shapes
-        if (tiles(256, 256) >= cus) id = wide ? 8 : 2;
-        else if (wide && tiles(256, 128) >= cus) id = 9;
-        else if (tiles(128, 192) >= cus && (!wide || tiles(128, 256) < cus)) id = wide ? 6 : 10;
-        else if (tiles(128, 128) >= cus / 2) id = wide ? 3 : 4;
-        else id = 11;
+        if (tiles(128, 128) >= cus / 2) {
+            // The cheapest of four tile shapes by rounds x tile area / efficiency, as in the int4 kernel.  With FP4
+            // the small tiles are far less efficient (their LDS traffic per matrix instruction is the bound), so
+            // 256 x 256 pays from about half of the compute units on.  Efficiencies relative to 256 x 256 and the
+            // cost of sharing a compute unit are fitted to a sweep of every tile over 12 outputs, whose fastest
+            // tile the model names in each.
+            auto rounds = [&](int64_t t) { return (double)((t + cus - 1) / cus); };
+            auto rounds_shared = [&](int64_t t) {          // two workgroups may share a compute unit
+                const int64_t pairs = (t - 1) / (2 * cus);
+                const double rest = (double)(t - 2 * cus * pairs) / (double)cus;       // (0, 2]
+                return 1.7 * (double)pairs + (rest <= 1.0 ? 1.0 : 1.5 + 0.2 * (rest - 1.0));
+            };
+            const double c256 = rounds(tiles(256, 256)) * (256.0 * 256.0) / 1.00;
+            const double c9 = wide ? rounds(tiles(256, 128)) * (256.0 * 128.0) / 0.72 : 1e30;     // 128-byte rows only
+            const double c192 = rounds_shared(tiles(128, 192)) * (128.0 * 192.0) / 0.55;
+            const double c128 = rounds_shared(tiles(128, 128)) * (128.0 * 128.0) / 0.47;
+            const double best = std::min(std::min(c256, c9), std::min(c192, c128));
+            if (best == c256) id = wide ? 8 : 2;
+            else if (best == c9) id = 9;
+            else if (best == c192) id = tiles(128, 192) > cus ? 5 : (wide ? 6 : 10);
+            else id = wide ? 3 : 4;
+        } else {
+            id = 11;
+        }
     }
     switch (id) {
         case 1: return launch_tile<256, 256, 2, 2, 128, 2>(a);
