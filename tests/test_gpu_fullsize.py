@@ -9,10 +9,21 @@ import torch
 
 import oracle
 import paper_2503_17513_amd as pme
-from parity_util import check_bf16, check_codes, check_scales, to_device, unpack_gpu
+from parity_util import check_bf16, check_codes, check_mx_gemm, check_mx_quant, check_scales, to_device, unpack_gpu
 from workloads import SPECS, custom_spec, make_workload
 
 pytestmark = pytest.mark.gpu
+
+
+def _sample_tokens(sp, rng):
+    """Every token, or 512 sampled tokens (first and last included) for the largest workload."""
+    if sp.T * sp.d_e > 2048 * 8704:
+        return np.unique(np.concatenate([[0, sp.T - 1], rng.choice(sp.T, 510, replace=False)]))
+    return np.arange(sp.T)
+
+
+def _sample_gemm_rows(sp, rng):
+    return np.unique(np.concatenate([[0, sp.T - 1], rng.choice(sp.T, min(sp.T, 62), replace=False)]))
 
 
 @pytest.mark.parametrize("name", ("C2", "C3", "C4", "C5"))
@@ -29,11 +40,7 @@ def test_full_workload(name):
     torch.cuda.synchronize()
 
     rng = np.random.default_rng(123)
-    # rotate + quantize: every token, or 512 sampled tokens (first and last included) for the largest
-    if sp.T * sp.d_e > 2048 * 8704:
-        rows = np.unique(np.concatenate([[0, sp.T - 1], rng.choice(sp.T, 510, replace=False)]))
-    else:
-        rows = np.arange(sp.T)
+    rows = _sample_tokens(sp, rng)
     ref_x = oracle.rotate_structured(wl.x[rows], sp.d_e)
     q_ref, s_ref = oracle.quantize_sym_int4(ref_x)
     q_gpu_all = unpack_gpu(qx)
@@ -42,7 +49,7 @@ def test_full_workload(name):
     check_codes(q_gpu_all[rows], q_ref, ref_x, s_ref)
 
     # GEMM: sampled token rows against all N outputs, from the library's own codes
-    grow = np.unique(np.concatenate([[0, sp.T - 1], rng.choice(sp.T, min(sp.T, 62), replace=False)]))
+    grow = _sample_gemm_rows(sp, rng)
     acc_ref = oracle.int_gemm(q_gpu_all[grow], wl.qw)
     assert np.array_equal(acc.cpu().numpy()[grow], acc_ref)
     y_ref = oracle.dequant_bf16(acc_ref, sx_all[grow], wl.sw)
@@ -50,6 +57,87 @@ def test_full_workload(name):
     # properties that hold at any size: every non-zero token reaches +-7, nothing leaves [-7, 7]
     assert q_gpu_all.min() >= -7 and q_gpu_all.max() <= 7
     assert np.all(np.abs(q_gpu_all).max(axis=1) == 7)
+
+
+@pytest.mark.parametrize("name", ("C2", "C3", "C4", "C5"))
+def test_full_workload_asymmetric(name):
+    """The layer with the paper's own activation quantizer (Section 4: per-token asymmetric int4) at the
+    benchmark sizes, automatic kernel and tile choice: scales, zero points and codes of the sampled tokens
+    against the oracle's quantizer, the fused call bit-equal to the chain of its parts, and sampled token rows
+    of the output against the oracle's GEMM and epilogue evaluated on the library's codes."""
+    wl = make_workload(name)
+    sp = wl.spec
+    xd = to_device(wl.x, sp.in_dtype)
+    wd = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+    swd = torch.from_numpy(wl.sw).cuda()
+    assert pme.get_path() == pme.PATH_AUTO
+    wsum = pme.weight_rowsum(wd)
+    assert np.array_equal(wsum.cpu().numpy(), wl.qw.astype(np.int64).sum(axis=1))
+    y = pme.expanded_linear_asym(xd, sp.d_e, wd, swd, wsum)
+    qx, sx, zx = pme.hadamard_expand_quant_asym(xd, sp.d_e)
+    y2 = pme.w4a4_gemm_asym(qx, sx, zx, wd, swd, wsum)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+
+    rng = np.random.default_rng(321)
+    rows = _sample_tokens(sp, rng)
+    ref_x = oracle.rotate_structured(wl.x[rows], sp.d_e)
+    q_ref, s_ref, z_ref = oracle.quantize_asym_int4(ref_x)
+    q_gpu_all = unpack_gpu(qx, signed=False)
+    sx_all, zx_all = sx.cpu().numpy(), zx.cpu().numpy()
+    check_scales(sx_all[rows], s_ref)
+    # a zero point may differ by one only where -lo / s sits at a rounding tie; such a token's codes are all
+    # shifted with it and are left out of the code comparison
+    zdiff = zx_all[rows] != z_ref
+    if zdiff.any():
+        lo = np.minimum(ref_x.min(axis=1), 0.0)
+        scaled = -lo / s_ref.astype(np.float64)
+        assert np.all(np.abs(np.abs(scaled - np.floor(scaled)) - 0.5)[zdiff] < 5e-5)
+        assert np.all(np.abs(zx_all[rows] - z_ref)[zdiff] == 1) and zdiff.sum() <= 1
+    keep = ~zdiff
+    check_codes(q_gpu_all[rows][keep], q_ref[keep], ref_x[keep], s_ref[keep])
+    assert q_gpu_all.max() <= 15 and np.all(q_gpu_all.max(axis=1) - q_gpu_all.min(axis=1) == 15)
+
+    grow = _sample_gemm_rows(sp, rng)
+    acc_ref = oracle.int_gemm(q_gpu_all[grow], wl.qw)
+    y_ref = oracle.dequant_asym_bf16(acc_ref, sx_all[grow], zx_all[grow], wl.qw, wl.sw)
+    check_bf16(y.to(torch.float32).cpu().numpy()[grow], y_ref)
+
+
+@pytest.mark.parametrize("name", ("C2", "C3", "C4", "C5"))
+def test_full_workload_mxfp4(name):
+    """The MXFP4 layer (Section 4, second setting) at the benchmark sizes, automatic kernel and tile choice.
+    Weights: seeded Gaussian W^T [N, d] on the bf16 grid, expanded and quantized by the library's own
+    weight-side call and checked on sampled channels against the oracle's quantizer; activations: the
+    workload's.  Sampled token rows of the output against the oracle's block-scaled GEMM on the library's codes."""
+    wl = make_workload(name, weights=False)
+    sp = wl.spec
+    rng = np.random.default_rng(77)
+    wt = torch.from_numpy(rng.standard_normal((sp.N, sp.d), dtype=np.float32) / np.float32(np.sqrt(sp.d)))
+    wt = wt.to(torch.bfloat16).to(torch.float32).numpy()
+    xd = to_device(wl.x, sp.in_dtype)
+    wtd = to_device(wt, "bf16")
+    assert pme.get_path() == pme.PATH_AUTO
+    qw, ew = pme.hadamard_expand_quant_mxfp4(wtd, sp.d_e)
+    y = pme.expanded_linear_mxfp4(xd, sp.d_e, qw, ew)
+    qx, ex = pme.hadamard_expand_quant_mxfp4(xd, sp.d_e)
+    y2 = pme.mxfp4_gemm(qx, ex, qw, ew)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), y2.view(torch.int16))
+
+    rows = _sample_tokens(sp, rng)
+    if rows.size > 512:
+        rows = np.unique(np.concatenate([[0, sp.T - 1], rng.choice(sp.T, 510, replace=False)]))
+    idx = torch.from_numpy(rows).cuda()
+    check_mx_quant(qx[idx], ex[idx], oracle.rotate_structured(wl.x[rows], sp.d_e))
+    chans = np.unique(np.concatenate([[0, sp.N - 1], rng.choice(sp.N, 254, replace=False)]))
+    cidx = torch.from_numpy(chans).cuda()
+    check_mx_quant(qw[cidx], ew[cidx], oracle.rotate_structured(wt[chans], sp.d_e))
+
+    grow = _sample_gemm_rows(sp, rng)
+    gidx = torch.from_numpy(grow).cuda()
+    check_mx_gemm(y[gidx].to(torch.float32).cpu().numpy(), oracle.unpack_fp4(qx[gidx].cpu().numpy()), ex[gidx].cpu().numpy(),
+                  oracle.unpack_fp4(qw.cpu().numpy()), ew.cpu().numpy())
 
 
 def test_code_matrix_beyond_4_gib():

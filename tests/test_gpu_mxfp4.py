@@ -5,7 +5,7 @@ import torch
 
 import oracle
 import paper_2503_17513_amd as pme
-from parity_util import check_xhat, to_device
+from parity_util import check_mx_gemm, check_mx_quant, to_device
 from workloads import custom_spec, make_workload
 
 pytestmark = pytest.mark.gpu
@@ -22,35 +22,6 @@ def _reset():
 def _acts(T, d, d_e, in_dtype="bf16", seed=0):
     spec = custom_spec(T, d, d_e, 8, in_dtype=in_dtype, act_dist="student_t3", outlier_frac=0.01, outlier_gain=50.0, seed=seed)
     return make_workload(spec, weights=False).x
-
-
-def check_mx_quant(qx: torch.Tensor, ex: torch.Tensor, ref_x: np.ndarray):
-    """Scale bytes equal except where the block maximum sits within 1e-5 of a power of two; on blocks with
-    equal scales the codes are equal except neighbouring-value flips at rounding ties (<= 1e-4 of the codes)."""
-    q_ref, e_ref = oracle.quantize_mxfp4(ref_x)
-    q = oracle.unpack_fp4(qx.cpu().numpy())
-    e = ex.cpu().numpy()
-    D, M = ref_x.shape
-    bad = e != e_ref
-    if bad.any():
-        amax = np.max(np.abs(ref_x.reshape(D, M // 32, 32)), axis=2)[bad]
-        frac, _ = np.frexp(amax)
-        assert np.all(np.minimum(np.abs(frac - 0.5), np.abs(frac - 1.0)) < 1e-5), "scale byte differs away from a power of two"
-        assert np.all(np.abs(e.astype(int) - e_ref.astype(int))[bad] == 1)
-        assert bad.sum() <= max(1, int(1e-5 * bad.size))
-    same = np.repeat(~bad, 32, axis=1)
-    flips = (q != q_ref) & same
-    n = int(flips.sum())
-    if n:
-        X = np.repeat(np.ldexp(1.0, e_ref.astype(np.int64) - 127), 32, axis=1)
-        scaled = np.abs(ref_x / X)[flips]
-        mids = np.array([0.25, 0.75, 1.25, 1.75, 2.5, 3.5, 5.0])
-        dist = np.min(np.abs(scaled[:, None] - mids[None, :]), axis=1)
-        assert np.all(dist < 5e-4), f"a flipped code is not at a rounding tie ({dist.max():.3e})"
-        dec_gap = np.abs(oracle.e2m1_decode(q[flips]) - oracle.e2m1_decode(q_ref[flips]))
-        assert np.all(dec_gap <= 2.0)
-        assert n <= max(1, int(1e-4 * q.size)), f"{n} flipped codes of {q.size}"
-    return n
 
 
 QUANT_CASES = [
@@ -91,14 +62,6 @@ def test_mxfp4_rejects_d_e_not_multiple_of_32():
     with pytest.raises(pme.PmeError) as e:
         pme.hadamard_expand_quant_mxfp4(x, 80)
     assert e.value.status == 2
-
-
-def check_mx_gemm(y_gpu, qx, ex, qw, ew):
-    """bf16 rounding (1e-2 relative) plus fp32 accumulation inside the matrix core, bounded by 2^-18 of the
-    sum of the magnitudes of the terms (K <= 2^14 terms, error grows like sqrt(K) 2^-24 of that sum)."""
-    y_ref, abs_sum = oracle.gemm_mxfp4(qx, ex, qw, ew, return_abs=True)
-    err = np.abs(y_gpu.astype(np.float64) - y_ref)
-    assert np.all(err <= 1e-2 * np.abs(y_ref) + 2.0 ** -18 * abs_sum), f"worst {np.max(err / (np.abs(y_ref) + 1e-30)):.3e}"
 
 
 GEMM_CASES = [("small_ragged", 50, 70, 96, (GENERIC,)), ("one_k_step", 40, 72, 128, (GENERIC, MFMA)),
