@@ -4,6 +4,11 @@
 One step = one pass of the whole hot path (zero-pad + Hadamard rotation + per-token int4
 quantization + int4 GEMM + dequantising epilogue) over one batch of synthetic activations
 that already sit in HBM.  Prints one JSON line.
+
+The headline workload is C5 (4096 tokens, 14336 -> 15360, 4096 outputs: the largest single-GPU
+configuration); the same line carries a record per other workload (C2, C3, and the decode shape C4,
+whose layer GB/s is the metric's decode half) and the measured ceilings the fractions are also
+quoted against.
 """
 from __future__ import annotations
 
@@ -119,11 +124,14 @@ def _cpu_baseline(wl, budget_s: float = 20.0):
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="C2", help="C1..C5 (default C2, the configuration the metric is quoted on)")
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--replays", type=int, default=5,
+                    help="timed replays of the HIP graph of K steps; ms_per_step is the median replay / K")
+    ap.add_argument("--workload", default="C5", help="C1..C5 (default C5, the largest single-GPU configuration)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--stages", action="store_true", help="also time each stage and every other workload")
+    ap.add_argument("--no-others", action="store_true", help="skip the records of the other workloads (profiling runs)")
+    ap.add_argument("--stages", action="store_true", help="accepted for compatibility: the per-workload stage records are always printed")
     ap.add_argument("--mxfp4", action="store_true",
                     help="also time the MXFP4 variant of the layer (the paper's second quantization setting)")
     ap.add_argument("--asym", action="store_true",
@@ -138,7 +146,7 @@ def main() -> int:
     ap.add_argument("--no-graph", action="store_true",
                     help="time the plain Python loop of library calls instead of a HIP graph replay of it")
     ap.add_argument("--no-probes", action="store_true",
-                    help="skip the two measured ceilings (streaming copy, back-to-back matrix-core instructions)")
+                    help="skip the measured ceilings (streaming copy and read, back-to-back matrix-core instructions, launch floor)")
     ap.add_argument("--cold", action="store_true",
                     help="also time the layer cycling through distinct operand sets larger than twice the 256 MB "
                          "last-level cache, so that nothing is served from cache")
@@ -161,7 +169,7 @@ def main() -> int:
         if sp.in_dtype == "bf16":
             x = x.to(torch.bfloat16)
         x = x.cuda()
-        qw = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+        qw = pme.pack_int4(torch.from_numpy(wl.qw))
         sw = torch.from_numpy(wl.sw).cuda()
         y = torch.empty((sp.T, sp.N), dtype=torch.bfloat16, device="cuda")
         ws = torch.empty((max(256, pme.workspace_bytes(sp.T, sp.d, sp.d_e, sp.N)),), dtype=torch.uint8, device="cuda")
@@ -169,17 +177,62 @@ def main() -> int:
         sx = torch.empty((sp.T,), dtype=torch.float32, device="cuda")
         return wl, dict(x=x, qw=qw, sw=sw, y=y, ws=ws, qx=qx, sx=sx)
 
+    def timed(fn, iters):
+        if not args.no_graph:
+            t = _graph_ms(fn, iters)
+            if t is not None:
+                return t
+        return _event_ms(fn, iters, 5)
+
     def stage_times(sp, b, iters):
         pme.hadamard_expand_quant(b["x"], sp.d_e, b["qx"], b["sx"])
         rot = lambda: pme.hadamard_expand_quant(b["x"], sp.d_e, b["qx"], b["sx"])
         gemm = lambda: pme.w4a4_gemm(b["qx"], b["sx"], b["qw"], b["sw"], b["y"])
-        # graph replays when the capture works (no host time between launches), else plain loops
-        t_rot = _graph_ms(rot, iters) or _event_ms(rot, iters, 5)
-        t_gemm = _graph_ms(gemm, iters) or _event_ms(gemm, iters, 5)
-        return t_rot, t_gemm
+        return timed(rot, iters), timed(gemm, iters)
+
+    def decode_layer_bytes(sp):
+        return sp.N * sp.d_e // 2 + 4 * sp.N + sp.T * sp.d * 2 + 2 * sp.T * sp.N
+
+    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    stored_traffic = {}
+    if os.path.exists(traffic_file):
+        with open(traffic_file) as f:
+            stored_traffic = json.load(f)
+
+    def traffic_of(key, stage, kernel_now):
+        """HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE, calibrated by the library's
+        1 GiB copy kernel; profiles/expanded_linear_<workload>.md), only if they were taken on the kernel
+        configuration that is being timed now: the stored record names the instantiation it belongs to."""
+        tr = stored_traffic.get(key, {}).get(stage)
+        if not tr:
+            return None, None
+        if kernel_now is not None and tr.get("kernel") != kernel_now:
+            return None, f"stored profile is of {tr.get('kernel')}, this run dispatches {kernel_now}: not used"
+        return tr["total_bytes"], tr
+
+    def workload_record(sp, b, t_layer, iters):
+        """Per-kernel times and roofline fractions of one workload (published peaks)."""
+        t_rot, t_gemm = stage_times(sp, b, iters)
+        ops = gemm_ops(sp)
+        rot_bytes = algorithmic_bytes_rotate_quant(sp)
+        rec = {"T": sp.T, "d": sp.d, "d_e": sp.d_e, "N": sp.N,
+               "layer_us": t_layer * 1e3, "layer_tops": ops / (t_layer * 1e-3) / 1e12,
+               "rotate_us": t_rot * 1e3, "rotate_gbs": rot_bytes / (t_rot * 1e-3) / 1e9,
+               "rotate_frac_hbm": rot_bytes / (t_rot * 1e-3) / 1e9 / PEAK_HBM_GBS,
+               "gemm_us": t_gemm * 1e3, "gemm_kernel": pme.gemm_plan(sp.T, sp.d_e, sp.N),
+               "gemm_tops": ops / (t_gemm * 1e-3) / 1e12, "gemm_gbs": algorithmic_bytes_gemm(sp) / (t_gemm * 1e-3) / 1e9}
+        if sp.T <= 32:
+            lb = decode_layer_bytes(sp)
+            rec.update({"bound": "hbm", "layer_bytes": lb, "layer_gbs": lb / (t_layer * 1e-3) / 1e9,
+                        "layer_frac_hbm": lb / (t_layer * 1e-3) / 1e9 / PEAK_HBM_GBS,
+                        "gemm_frac_hbm": lb / (t_gemm * 1e-3) / 1e9 / PEAK_HBM_GBS})
+        else:
+            rec.update({"bound": "mfma", "gemm_frac_int8_peak": ops / (t_gemm * 1e-3) / 1e12 / PEAK_INT8_TOPS,
+                        "layer_frac_int8_peak": ops / (t_layer * 1e-3) / 1e12 / PEAK_INT8_TOPS})
+        return rec, t_rot, t_gemm
 
     def measured_ceilings(fp4: bool, copy_launches: int):
-        """The two microbenchmarks the roofline fractions are also quoted against."""
+        """The microbenchmarks the roofline fractions are also quoted against."""
         res = {}
         src = torch.empty((1 << 30,), dtype=torch.uint8, device="cuda").fill_(1)
         dst = torch.empty_like(src)
@@ -187,9 +240,18 @@ def main() -> int:
         t_copy = _event_ms(lambda: pme.probe_copy(src, dst), copy_launches)
         res["probe_copy"] = {"bytes_read": 1 << 30, "bytes_written": 1 << 30, "us": t_copy * 1e3,
                              "gbs": 2 * (1 << 30) / (t_copy * 1e-3) / 1e9}
-        del src, dst
+        del dst
+        sink = torch.zeros((2048 * 256,), dtype=torch.int32, device="cuda")
+        pme.probe_read(src, sink)
+        t_read = _event_ms(lambda: pme.probe_read(src, sink), max(2, copy_launches))
+        res["probe_read"] = {"bytes_read": 1 << 30, "bytes_written": sink.numel() * 4, "us": t_read * 1e3,
+                             "gbs": (1 << 30) / (t_read * 1e-3) / 1e9}
+        del src
         torch.cuda.empty_cache()
-        sink = torch.zeros((512 * 256,), dtype=torch.int32, device="cuda")
+        # a chain of kernels that do nothing, captured in a graph like the timed steps: microseconds per dependent launch
+        t_launch = _graph_ms(pme.probe_launch, 200)
+        if t_launch is not None:
+            res["probe_launch"] = {"us_per_dependent_launch_in_a_graph": t_launch * 1e3}
         # near-constant operands reach the published peak; pseudo-random codes (the bytes a GEMM really feeds the
         # pipe) run slower, the matrix pipe being power-limited: both ceilings are printed
         kinds = ((0, "probe_mfma_int8"), (2, "probe_mfma_int8_random_codes"))
@@ -220,37 +282,36 @@ def main() -> int:
     plain_ms = start.elapsed_time(stop) / args.steps
     # The same K steps captured once into a HIP graph and replayed: what a serving loop would do, and it
     # takes the host's launch path (a ctypes call and two kernel launches per step) out of the timed region.
-    # One untimed replay, then exactly one timed replay of K steps.
+    # One untimed replay, then `replays` timed replays of exactly K steps each; the median replay is reported.
     ms, launch = plain_ms, "plain loop of K library calls"
     if not args.no_graph:
-        g_ms = _graph_ms(step, args.steps, 1)
+        g_ms = _graph_ms(step, args.steps, max(1, args.replays))
         if g_ms is not None:
-            ms, launch = g_ms, "HIP graph of K library calls, one timed replay"
+            ms, launch = g_ms, f"HIP graph of K library calls, median of {max(1, args.replays)} timed replays"
 
     ops = gemm_ops(sp)
-    t_rot, t_gemm = stage_times(sp, b, max(20, args.steps))
+    iters = max(20, min(args.steps, 200))
+    rec, t_rot, t_gemm = workload_record(sp, b, ms, iters)
     decode = sp.T <= 32
+    kernel_now = rec["gemm_kernel"]
     if decode:
-        # memory-bound shape: the whole layer is priced against HBM bandwidth
-        layer_bytes = sp.N * sp.d_e // 2 + 4 * sp.N + sp.T * sp.d * 2 + 2 * sp.T * sp.N
+        # memory-bound shape: the GEMM (the dominant kernel) is priced against HBM bandwidth on the layer's bytes
+        layer_bytes = decode_layer_bytes(sp)
         ach = layer_bytes / (t_gemm * 1e-3) / 1e9
-        roof = {"bound": "hbm", "kernel": "w4a4_gemm", "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_launch_us": t_gemm * 1e3}
+        roof = {"bound": "hbm", "kernel": kernel_now, "achieved": ach, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                "frac": ach / PEAK_HBM_GBS, "traffic": None, "avg_launch_us": t_gemm * 1e3, "algorithmic_bytes": layer_bytes}
     else:
         ach = ops / (t_gemm * 1e-3) / 1e12
-        roof = {"bound": "mfma", "kernel": "w4a4_gemm", "achieved": ach, "peak": PEAK_INT8_TOPS, "unit": "TFLOP/s",
+        roof = {"bound": "mfma", "kernel": kernel_now, "achieved": ach, "peak": PEAK_INT8_TOPS, "unit": "TOP/s",
                 "frac": ach / PEAK_INT8_TOPS, "traffic": None, "avg_launch_us": t_gemm * 1e3,
                 "algorithmic_ops": ops, "algorithmic_bytes": algorithmic_bytes_gemm(sp),
-                "note": "int8 MFMA ops (2 per multiply-add) over the expanded d_e"}
-    traffic_file = os.path.join(ROOT, "profiles", "hbm_traffic.json")
-    if os.path.exists(traffic_file):
-        with open(traffic_file) as f:
-            tr = json.load(f).get(sp.name, {}).get("w4a4_gemm")
-        if tr:
-            # HBM bytes per launch from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE), calibrated by the
-            # library's 1 GiB copy kernel; see profiles/expanded_linear_<workload>.md
-            roof["traffic"] = tr["total_bytes"]
-            roof["traffic_detail"] = tr
+                "note": "int8 MFMA ops (2 per multiply-add) over the expanded d_e; dtype peak: int8 dense 5.0 POP/s"}
+    tr_bytes, tr_detail = traffic_of(sp.name, "w4a4_gemm", kernel_now)
+    roof["traffic"] = tr_bytes
+    if isinstance(tr_detail, dict):
+        roof["traffic_detail"] = tr_detail
+    elif tr_detail:
+        roof["traffic_note"] = tr_detail
     rot_bytes = algorithmic_bytes_rotate_quant(sp)
     rot_gbs = rot_bytes / (t_rot * 1e-3) / 1e9
 
@@ -258,7 +319,7 @@ def main() -> int:
     if not args.no_probes:
         probes = measured_ceilings(args.mxfp4, 5 if args.probe_copy else 2)
         if decode:
-            roof["measured_peak"] = probes["probe_copy"]["gbs"]
+            roof["measured_peak"] = probes["probe_read"]["gbs"]
         else:
             roof["measured_peak"] = probes["probe_mfma_int8"]["tops"]
             roof["measured_peak_random_codes"] = probes["probe_mfma_int8_random_codes"]["tops"]
@@ -277,32 +338,35 @@ def main() -> int:
         "dtype": "int8", "data": "synthetic",
         "config": {"workload": f"{sp.name}: T={sp.T} d={sp.d} d_e={sp.d_e} N={sp.N} in={sp.in_dtype}",
                    "step": "pme_expanded_linear (rotate+quantize, then W4A4 GEMM with bf16 epilogue)",
-                   "launch": launch},
+                   "launch": launch, "replays": max(1, args.replays)},
         "roofline": roof,
         "rotate_quant": {"bound": "hbm", "kernel": "hadamard_expand_quant", "achieved": rot_gbs, "peak": PEAK_HBM_GBS,
                          "unit": "GB/s", "frac": rot_gbs / PEAK_HBM_GBS, "avg_launch_us": t_rot * 1e3,
                          "algorithmic_bytes": rot_bytes},
+        "workloads": {sp.name: rec},
     }
-    if args.stages:
-        others = {}
+    tr_rot, _ = traffic_of(sp.name, "hadamard_expand_quant", None)
+    out["rotate_quant"]["traffic"] = tr_rot
+    if not args.no_others:
         for name in SPECS:
-            if name == sp.name:
+            if name in (sp.name, "C1"):
                 continue
             wl2, b2 = prepare(name)
             s2 = wl2.spec
             layer2 = lambda: pme.expanded_linear(b2["x"], s2.d_e, b2["qw"], b2["sw"], b2["y"], b2["ws"])
-            for _ in range(20):
+            for _ in range(10):
                 layer2()
-            it = 50
-            t_all = _graph_ms(layer2, it) or _event_ms(layer2, it, 5)
-            tr, tg = stage_times(s2, b2, it)
-            others[name] = {"layer_us": t_all * 1e3, "layer_tops": gemm_ops(s2) / (t_all * 1e-3) / 1e12,
-                            "rotate_us": tr * 1e3, "rotate_gbs": algorithmic_bytes_rotate_quant(s2) / (tr * 1e-3) / 1e9,
-                            "gemm_us": tg * 1e3, "gemm_tops": gemm_ops(s2) / (tg * 1e-3) / 1e12,
-                            "gemm_gbs": algorithmic_bytes_gemm(s2) / (tg * 1e-3) / 1e9}
+            it = 100
+            rec2, _, _ = workload_record(s2, b2, timed(layer2, it), it)
+            out["workloads"][name] = rec2
             del wl2, b2
             torch.cuda.empty_cache()
-        out["other_workloads"] = others
+    # the metric's decode half: the memory-bound shape's whole layer against HBM bandwidth
+    for name, r in out["workloads"].items():
+        if r.get("bound") == "hbm":
+            out["decode"] = {"workload": name, "metric": "layer HBM GB/s (weights + activations + outputs once)",
+                             "value": r["layer_gbs"], "unit": "GB/s", "frac": r["layer_frac_hbm"], "layer_us": r["layer_us"],
+                             "rotate_us": r["rotate_us"], "gemm_us": r["gemm_us"], "algorithmic_bytes": r["layer_bytes"]}
     if args.paper_sizes:
         rows = []
         for d, N, sizes in ((8192, 2048, (8704, 8960, 9728, 10240, 12288)), (14336, 4096, (15360, 18432, 19968, 22016))):
@@ -339,33 +403,34 @@ def main() -> int:
         for f in (layer_a, rot_a, gemm_a):
             for _ in range(3):
                 f()
-        it = max(20, args.steps)
-        t_l, t_r, t_g = (_graph_ms(f, it) or _event_ms(f, it, 5) for f in (layer_a, rot_a, gemm_a))
+        t_l, t_r, t_g = (timed(f, iters) for f in (layer_a, rot_a, gemm_a))
         out["asym"] = {"layer_us": t_l * 1e3, "layer_tops": ops / (t_l * 1e-3) / 1e12, "rotate_quant_us": t_r * 1e3,
-                       "gemm_us": t_g * 1e3, "gemm_tops": ops / (t_g * 1e-3) / 1e12}
+                       "gemm_us": t_g * 1e3, "gemm_tops": ops / (t_g * 1e-3) / 1e12,
+                       "gemm_kernel": pme.gemm_plan(sp.T, sp.d_e, sp.N, 1)}
     if args.mxfp4:
         wt = torch.randn((sp.N, sp.d), device="cuda").to(torch.bfloat16)     # any weights: timing only
         qw4, ew4 = pme.hadamard_expand_quant_mxfp4(wt, sp.d_e)
         qx4, ex4 = pme.hadamard_expand_quant_mxfp4(b["x"], sp.d_e)
         for _ in range(5):
             pme.expanded_linear_mxfp4(b["x"], sp.d_e, qw4, ew4, b["y"], b["ws"])
-        it = max(20, args.steps)
         layer_m = lambda: pme.expanded_linear_mxfp4(b["x"], sp.d_e, qw4, ew4, b["y"], b["ws"])
         rot_m = lambda: pme.hadamard_expand_quant_mxfp4(b["x"], sp.d_e, qx4, ex4)
         gemm_m = lambda: pme.mxfp4_gemm(qx4, ex4, qw4, ew4, b["y"])
-        t_l, t_r, t_g = (_graph_ms(f, it) or _event_ms(f, it, 5) for f in (layer_m, rot_m, gemm_m))
+        t_l, t_r, t_g = (timed(f, iters) for f in (layer_m, rot_m, gemm_m))
+        mx_kernel = pme.gemm_plan(sp.T, sp.d_e, sp.N, 2)
         out["mxfp4"] = {"layer_us": t_l * 1e3, "layer_tflops": ops / (t_l * 1e-3) / 1e12, "rotate_quant_us": t_r * 1e3,
-                        "gemm_us": t_g * 1e3, "gemm_tflops": ops / (t_g * 1e-3) / 1e12, "gemm_peak_tflops": 10100.0,
-                        "gemm_frac": ops / (t_g * 1e-3) / 1e12 / 10100.0, "gemm_traffic": None}
-        if os.path.exists(traffic_file):
-            with open(traffic_file) as f:
-                tr4 = json.load(f).get(sp.name + "_mxfp4", {}).get("w4a4_gemm")
-            if tr4:
-                out["mxfp4"]["gemm_traffic"] = tr4["total_bytes"]
+                        "gemm_us": t_g * 1e3, "gemm_kernel": mx_kernel, "gemm_tflops": ops / (t_g * 1e-3) / 1e12,
+                        "gemm_peak_tflops": 10100.0, "gemm_frac": ops / (t_g * 1e-3) / 1e12 / 10100.0, "gemm_traffic": None}
+        out["mxfp4"]["gemm_traffic"], _ = traffic_of(sp.name + "_mxfp4", "w4a4_gemm", mx_kernel)
     if probes:
-        out["rotate_quant"]["measured_peak"] = probes["probe_copy"]["gbs"]
-        out["rotate_quant"]["frac_of_measured"] = rot_gbs / probes["probe_copy"]["gbs"]
+        # rotate + quantize reads four bytes for each one it writes: the read-only stream is its yardstick
+        out["rotate_quant"]["measured_peak"] = probes["probe_read"]["gbs"]
+        out["rotate_quant"]["frac_of_measured"] = rot_gbs / probes["probe_read"]["gbs"]
+        out["rotate_quant"]["frac_of_measured_copy"] = rot_gbs / probes["probe_copy"]["gbs"]
         out["measured_ceilings"] = probes
+        if "decode" in out and "probe_launch" in probes:
+            # two dependent launches per layer: what two kernels that do nothing cost in the same kind of graph
+            out["decode"]["two_empty_launches_us"] = 2 * probes["probe_launch"]["us_per_dependent_launch_in_a_graph"]
         if args.mxfp4 and "probe_mfma_fp4" in probes:
             out["mxfp4"]["gemm_measured_peak_tflops"] = probes["probe_mfma_fp4"]["tops"]
             out["mxfp4"]["gemm_measured_peak_random_codes_tflops"] = probes["probe_mfma_fp4_random_codes"]["tops"]

@@ -13,8 +13,8 @@
  * block of order b (b - 1 a prime congruent to 3 mod 4, or 7^3; b = 1 for a pure power
  * of two; supported: 1, 12, 20, 60, 68, 72, 132, 140, 152, 312, 344) Kronecker the
  * natural-order Sylvester matrix; matrix index i = a * 2^k + c.
- * The paper leaves the construction open ("a deterministic Hadamard matrix",
- * Section 4); pme_base_block exports the block actually used.
+ * Section 4 only asks for a deterministic Hadamard matrix and does not fix the
+ * construction; pme_base_block exports the block actually used.
  *
  * Conventions shared by every entry point unless stated otherwise:
  *  - Pointers named in the comments as DEVICE are HIP device memory owned by the
@@ -26,7 +26,8 @@
  *    once before capturing it in a HIP graph.
  *  - Arguments are validated on the host before any HIP call.  A status other than
  *    PME_OK means nothing was launched (PME_ERR_HIP excepted: a launch was refused by
- *    the runtime).  No C++ exception crosses this boundary.
+ *    the runtime); the fused pme_expanded_linear* calls ask both of their stages whether a
+ *    kernel takes the shape before they launch the first.  No C++ exception crosses this boundary.
  *  - Packed int4: byte j/2 of a row holds code j (even j) in its low nibble and code
  *    j+1 in its high nibble, each a 4-bit two's-complement integer (unsigned 0..15 for
  *    the asymmetric activation variant).
@@ -34,7 +35,9 @@
  *  - Outputs must not alias inputs.
  *  - Size limits: T and N below 2^31, d_e at most 2^20 (PME_ERR_SHAPE beyond).  Operands of any byte size within
  *    those limits are accepted; a GEMM whose packed activations or weights exceed 4 GiB is enqueued as several
- *    launches over slices of tokens or output channels, with the same results.
+ *    launches over slices of tokens or output channels, with the same results.  The matrix-core int4 GEMMs hold
+ *    256 x the exact sum in int32 and take d_e < 2^17 (256 * 64 * d_e < 2^31); from d_e = 2^17 on the plain-ALU
+ *    kernel runs (PME_ERR_UNSUPPORTED_PATH if the matrix-core path was forced).
  */
 #ifndef PME_H
 #define PME_H
@@ -99,7 +102,8 @@ pme_status pme_hadamard_expand_quant_asym(const void* x, pme_dtype xt, int64_t T
  *   output channel, i.e. the transpose of the paper's W_hat), sw DEVICE [N].
  *   y  DEVICE out [T, N] bf16 row-major, ldy elements between rows (ldy >= N).
  * The sum is exact int32 (|sum| <= 64 * d_e).  Alignment: qx, qw to 4 bytes (16 for the
- * MFMA path), y to 2 bytes.  T == 0 or N == 0 is a no-op.
+ * MFMA path), y to 2 bytes.  T == 0 or N == 0 is a no-op.  The call needs no workspace:
+ * partial sums never leave registers and LDS.
  */
 pme_status pme_w4a4_gemm(const uint8_t* qx, const float* sx, const uint8_t* qw, const float* sw,
                          int64_t T, int64_t d_e, int64_t N, void* y_bf16, int64_t ldy, void* stream);
@@ -113,13 +117,16 @@ pme_status pme_w4a4_gemm_asym(const uint8_t* qx, const float* sx, const int32_t*
                               const float* sw, const int32_t* wsum, int64_t T, int64_t d_e, int64_t N,
                               void* y_bf16, int64_t ldy, void* stream);
 
-/* wsum[n] = sum_j qw[n][j] for packed signed weight codes.  qw DEVICE [N, d_e/2], wsum DEVICE out [N]. */
+/* Offline companion of the asymmetric quantizer of Section 4: wsum[n] = sum_j qw[n][j] for packed signed weight
+ * codes, the factor of the zero-point correction above.  qw DEVICE [N, d_e/2], wsum DEVICE out [N]. */
 pme_status pme_weight_rowsum(const uint8_t* qw, int64_t N, int64_t d_e, int32_t* wsum, void* stream);
 
 /*
- * The whole expanded layer in one call: pme_hadamard_expand_quant followed by
+ * The whole expanded layer in one call (Section 3: the inference-time product Q(X H_hat) Q(H_hat^T W), with the
+ * per-token / per-channel scales of Section 4): pme_hadamard_expand_quant followed by
  * pme_w4a4_gemm, the codes and scales passing through `workspace`
- * (DEVICE, 256-byte aligned, at least pme_workspace_bytes(T, d, d_e, N) bytes).
+ * (DEVICE, 256-byte aligned, at least pme_workspace_bytes(T, d, d_e, N) bytes; contents undefined afterwards).
+ * Arguments as in the two calls.  PME_ERR_WORKSPACE if the workspace is too small.
  */
 pme_status pme_expanded_linear(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
                                int64_t d_e, const uint8_t* qw, const float* sw, int64_t N,
@@ -172,30 +179,52 @@ pme_status pme_expanded_linear_mxfp4(const void* x, pme_dtype xt, int64_t T, int
                                      void* y_bf16, int64_t ldy, void* workspace, size_t workspace_bytes,
                                      void* stream);
 
-/* Bytes of workspace the pme_expanded_linear* calls need (one size serves all three; 0 on invalid sizes). */
+/* Bytes of workspace the pme_expanded_linear* calls need for the quantized activations of Section 3's Q(X H_hat):
+ * packed codes [T, d_e/2], per-token scales (or MXFP4 scale bytes) and zero points, each part 256-byte aligned
+ * (one size serves all three calls; 0 on invalid sizes).  N is accepted for symmetry and does not enter. */
 size_t pme_workspace_bytes(int64_t T, int64_t d, int64_t d_e, int64_t N);
 
 /* ---- parity / debug exports ---- */
 
-/* X_hat itself (gamma applied), fp32: xhat DEVICE out [T, d_e] dense. */
+/* X_hat = X H_hat itself (Section 3; gamma = 1/sqrt(d_e) applied), fp32, unquantized: xhat DEVICE out
+ * [T, d_e] dense.  x as in pme_hadamard_expand_quant.  Applied to the rows of W^T it is W_hat^T. */
 pme_status pme_hadamard_expand_f32(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
                                    int64_t d_e, float* xhat, void* stream);
 
-/* The raw int32 accumulators of the GEMM: acc DEVICE out [T, N] dense. */
+/* The raw int32 accumulators of Section 3's Q(X_hat) Q(W_hat), before any scale: acc[t][n] = sum_j qx[t][j] qw[n][j]
+ * for signed codes, exact.  qx DEVICE [T, d_e/2], qw DEVICE [N, d_e/2], acc DEVICE out [T, N] dense. */
 pme_status pme_w4a4_gemm_i32(const uint8_t* qx, const uint8_t* qw, int64_t T, int64_t d_e, int64_t N,
                              int32_t* acc, void* stream);
 
-/* d_e = b * 2^k with the smallest supported b; HOST pointers.  PME_ERR_UNSUPPORTED_ORDER if none. */
+/* The factorisation of the expanded size M = d_e of Section 3 that the Hadamard matrix is built from:
+ * d_e = b * 2^k with the smallest supported b; b, k HOST out.  PME_ERR_UNSUPPORTED_ORDER if none. */
 pme_status pme_factor_order(int64_t d_e, int32_t* b, int32_t* k);
 
-/* The +-1 Paley block of order b, row-major b x b, written to HOST memory out_bxb. */
+/* The +-1 Paley block P_b of the Hadamard matrix H = P_b (x) S_{2^k} behind Section 3's H_hat (Section 4 leaves the
+ * construction open), row-major b x b, written to HOST memory out_bxb (b * b bytes).  P = I + [[0, 1^T], [-1, Q]],
+ * Q[i][j] = chi(x_i - x_j) over GF(b - 1).  PME_ERR_UNSUPPORTED_ORDER for an order not in the list above. */
 pme_status pme_base_block(int64_t b, int8_t* out_bxb);
+
+/* Input preparation for the weight operand (Section 4: int4 weights; two codes per byte as stated under
+ * "Packed int4" above): codes DEVICE [rows, K] int8 in [-8, 7] (only the low 4 bits are kept), packed DEVICE out
+ * [rows, K/2].  K even, both dense. */
+pme_status pme_pack_int4(const int8_t* codes, int64_t rows, int64_t K, uint8_t* packed, void* stream);
 
 /* ---- measurement helpers ---- */
 
-/* Plain device copy of `bytes` (multiple of 16) from src to dst, both DEVICE and 16-byte aligned:
- * the known-size kernel used to calibrate the profiler's HBM byte counters. */
+/* Plain device copy of `bytes` (multiple of 16) from src to dst, both DEVICE and 16-byte aligned, four 16-byte
+ * loads in flight per lane: the known-size kernel that calibrates the profiler's HBM byte counters and gives the
+ * measured read + write streaming rate. */
 pme_status pme_probe_copy(const void* src, void* dst, size_t bytes, void* stream);
+
+/* Read-only stream of `bytes` (multiple of 16) from src (DEVICE, 16-byte aligned), same load pattern as the copy:
+ * the measured ceiling for a stage that mostly reads, as rotate + quantize does (four fifths of its bytes).
+ * sink: DEVICE out, at least 2048 * 256 uint32 (one checksum per lane, the probe's only writes). */
+pme_status pme_probe_read(const void* src, size_t bytes, uint32_t* sink, size_t sink_elems, void* stream);
+
+/* Enqueues a kernel that does nothing (one wave): timing a chain of them gives the cost of a dependent launch,
+ * the floor under a layer that is two tiny kernels, as the decode shape is. */
+pme_status pme_probe_launch(void* stream);
 
 /* Back-to-back independent matrix-core instructions, nothing else in the loop: the measured ceiling the
  * GEMMs are priced against next to the published peak.  kind 0: v_mfma_i32_32x32x32_i8 (the int4 path's
@@ -213,6 +242,13 @@ pme_status pme_probe_mfma(int kind, int32_t* out, size_t out_elems, int iters, d
  * 1..24 = a fixed entry of the int4 kernel's tile table, 100 + (1..11) = of the MXFP4 kernel's; 0 resets
  * both).  Process-wide, not thread-safe. */
 void pme_set_gemm_tile(int id);
+
+/* Which kernel configuration the GEMM of a T x d_e x N layer would run under the current path and tile settings,
+ * as the instantiation's name in a profiler's kernel trace (e.g. "k_gemm_mfma<256, 256, 2, 2, 128, 2, 0, 1, false>").
+ * variant 0: symmetric int4, 1: asymmetric int4, 2: MXFP4.  name HOST out, at most name_len bytes with the
+ * terminating zero.  Nothing is launched.  The benchmark uses it to check that stored profiler figures belong to
+ * the kernel it is timing. */
+pme_status pme_gemm_plan(int variant, int64_t T, int64_t d_e, int64_t N, char* name, size_t name_len);
 
 void pme_set_path(pme_path p);
 pme_path pme_get_path(void);

@@ -17,7 +17,8 @@ F32, BF16 = 0, 1
 EXPORTS = ("pme_hadamard_expand_quant", "pme_expand_quantize_weights", "pme_hadamard_expand_quant_mxfp4",
            "pme_mxfp4_gemm", "pme_expanded_linear_mxfp4", "pme_hadamard_expand_quant_asym", "pme_w4a4_gemm", "pme_w4a4_gemm_asym",
            "pme_weight_rowsum", "pme_expanded_linear", "pme_expanded_linear_asym", "pme_workspace_bytes", "pme_hadamard_expand_f32",
-           "pme_w4a4_gemm_i32", "pme_factor_order", "pme_base_block", "pme_probe_copy", "pme_probe_mfma", "pme_set_path", "pme_set_gemm_tile",
+           "pme_w4a4_gemm_i32", "pme_factor_order", "pme_base_block", "pme_pack_int4", "pme_gemm_plan", "pme_probe_copy", "pme_probe_read", "pme_probe_launch", "pme_probe_mfma",
+           "pme_set_path", "pme_set_gemm_tile",
            "pme_get_path", "pme_status_string", "pme_version")
 
 
@@ -57,7 +58,11 @@ def lib() -> C.CDLL:
     L.pme_workspace_bytes.restype = sz
     L.pme_factor_order.argtypes = [i64, C.POINTER(C.c_int32), C.POINTER(C.c_int32)]
     L.pme_base_block.argtypes = [i64, vp]
+    L.pme_pack_int4.argtypes = [vp, i64, i64, vp, vp]
+    L.pme_gemm_plan.argtypes = [i32, i64, i64, i64, C.c_char_p, sz]
     L.pme_probe_copy.argtypes = [vp, vp, sz, vp]
+    L.pme_probe_read.argtypes = [vp, sz, vp, sz, vp]
+    L.pme_probe_launch.argtypes = [vp]
     L.pme_probe_mfma.argtypes = [i32, vp, sz, i32, C.POINTER(C.c_double), vp]
     L.pme_set_path.argtypes = [i32]
     L.pme_set_gemm_tile.argtypes = [i32]
@@ -306,6 +311,15 @@ def probe_copy(src: torch.Tensor, dst: torch.Tensor) -> None:
     _check(lib().pme_probe_copy(_dev(src, "src"), _dev(dst, "dst"), nbytes, _stream()), "pme_probe_copy")
 
 
+def probe_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(lib().pme_probe_read(_dev(src, "src"), nbytes, _dev(sink, "sink"), sink.numel(), _stream()), "pme_probe_read")
+
+
+def probe_launch() -> None:
+    _check(lib().pme_probe_launch(_stream()), "pme_probe_launch")
+
+
 def probe_mfma(kind: int, out: torch.Tensor, iters: int) -> float:
     """Launch the matrix-core probe (kind 0 int8, 1 FP4; 2, 3 the same on pseudo-random codes) and return the
     operation count of the launch."""
@@ -315,8 +329,21 @@ def probe_mfma(kind: int, out: torch.Tensor, iters: int) -> float:
     return ops.value
 
 
-def pack_int4_codes(codes: torch.Tensor) -> torch.Tensor:
-    """Input preparation (not part of the hot path): int8 codes [.., K] in [-8, 7] -> packed uint8 [.., K/2],
-    even index in the low nibble."""
-    u = (codes.to(torch.int16) & 0xF).to(torch.uint8)
-    return (u[..., 0::2] | (u[..., 1::2] << 4)).contiguous()
+def pack_int4(codes: torch.Tensor) -> torch.Tensor:
+    """int8 codes [rows, K] in [-8, 7] -> packed uint8 [rows, K/2] on the device (even index in the low nibble).
+    A host tensor is copied to the current device first."""
+    if codes.dtype != torch.int8 or codes.dim() != 2:
+        raise TypeError("codes must be an int8 [rows, K] tensor")
+    codes = codes.cuda().contiguous()
+    rows, K = codes.shape
+    packed = torch.empty((rows, K // 2), dtype=torch.uint8, device=codes.device)
+    _check(lib().pme_pack_int4(_dev(codes, "codes"), rows, K, packed.data_ptr(), _stream()), "pme_pack_int4")
+    return packed
+
+
+def gemm_plan(T: int, d_e: int, N: int, variant: int = 0) -> str:
+    """Name of the kernel instantiation the GEMM of this shape would run (variant 0 symmetric int4, 1 asymmetric,
+    2 MXFP4), as a profiler prints it."""
+    buf = C.create_string_buffer(128)
+    _check(lib().pme_gemm_plan(int(variant), T, d_e, N, buf, len(buf)), "pme_gemm_plan")
+    return buf.value.decode()

@@ -145,10 +145,15 @@ pme_status launch_groups(const GemmArgs& a) {
 }  // namespace
 
 pme_status launch_gemm_decode(const GemmArgs& a) {
-    // at most 64 tokens, whole 64-byte chunks, 16-byte aligned rows
-    if (a.T > 64 || a.d_e % 128 || a.d_e > (1 << 17)) return PME_ERR_UNSUPPORTED_PATH;
+    // at most 64 tokens, whole 64-byte chunks, 16-byte aligned rows, the x256 accumulator in range
+    // (256 * 64 * d_e < 2^31 needs d_e < 2^17; the asymmetric correction is applied after the shift)
+    if (a.T > 64 || a.d_e % 128 || a.d_e >= (1 << 17)) return PME_ERR_UNSUPPORTED_PATH;
     if ((reinterpret_cast<uintptr_t>(a.qx) & 15) || (reinterpret_cast<uintptr_t>(a.qw) & 15)) return PME_ERR_UNSUPPORTED_PATH;
     if (a.zx && a.out_i32) return PME_ERR_UNSUPPORTED_PATH;
+    if (a.dry) {
+        if (a.plan) *a.plan = "k_gemm_decode";
+        return PME_OK;
+    }
     if (a.T <= 16) return launch_groups<1>(a);
     if (a.T <= 32) return launch_groups<2>(a);
     if (a.T <= 48) return launch_groups<3>(a);

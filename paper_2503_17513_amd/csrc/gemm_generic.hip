@@ -3,6 +3,8 @@
 // does not take and the second implementation the tests cross-check it with.
 #include "pme_internal.h"
 
+#include <algorithm>
+
 namespace pme {
 namespace {
 
@@ -15,23 +17,25 @@ k_gemm_generic(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
                const int32_t* __restrict__ zx, const int32_t* __restrict__ wsum,
                int T, int N, int kb, void* __restrict__ out, int64_t ldo, int out_i32) {
     const int n = blockIdx.x * 16 + (threadIdx.x & 15);
-    const int t = blockIdx.y * 16 + (threadIdx.x >> 4);
-    if (n >= N || t >= T) return;
-    const uint8_t* ar = qx + (int64_t)t * kb;
+    if (n >= N) return;
     const uint8_t* wr = qw + (int64_t)n * kb;
-    int acc = 0;
-    for (int p = 0; p < kb; ++p) {
-        const uint32_t av = ar[p], wv = wr[p];
-        const int a0 = ASYM ? (int)(av & 0xF) : sext4(av & 0xF);
-        const int a1 = ASYM ? (int)(av >> 4) : sext4(av >> 4);
-        acc += a0 * sext4(wv & 0xF) + a1 * sext4(wv >> 4);
-    }
-    if (ASYM) acc -= zx[t] * wsum[n];
-    if (out_i32) {
-        static_cast<int32_t*>(out)[(int64_t)t * ldo + n] = acc;
-    } else {
-        const float y = (float)acc * sx[t] * sw[n];
-        static_cast<uint16_t*>(out)[(int64_t)t * ldo + n] = f32_to_bf16_bits(y);
+    // blocks of 16 tokens: the grid's y extent is capped (65535), so a workgroup walks its share of them
+    for (int64_t t = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 4); t < T; t += (int64_t)gridDim.y * 16) {
+        const uint8_t* ar = qx + t * kb;
+        int acc = 0;
+        for (int p = 0; p < kb; ++p) {
+            const uint32_t av = ar[p], wv = wr[p];
+            const int a0 = ASYM ? (int)(av & 0xF) : sext4(av & 0xF);
+            const int a1 = ASYM ? (int)(av >> 4) : sext4(av >> 4);
+            acc += a0 * sext4(wv & 0xF) + a1 * sext4(wv >> 4);
+        }
+        if (ASYM) acc -= zx[t] * wsum[n];
+        if (out_i32) {
+            static_cast<int32_t*>(out)[t * ldo + n] = acc;
+        } else {
+            const float y = (float)acc * sx[t] * sw[n];
+            static_cast<uint16_t*>(out)[t * ldo + n] = f32_to_bf16_bits(y);
+        }
     }
 }
 
@@ -48,11 +52,29 @@ k_weight_rowsum(const uint8_t* __restrict__ qw, int kb, int32_t* __restrict__ ws
     if (lane == 0) wsum[n] = s;
 }
 
+// Two 4-bit two's-complement codes per byte, even index in the low nibble.
+__global__ void __launch_bounds__(256)
+k_pack_int4(const int8_t* __restrict__ codes, int64_t pairs, uint8_t* __restrict__ packed) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < pairs; i += (int64_t)gridDim.x * 256) {
+        const uint32_t lo = (uint32_t)codes[2 * i] & 0xFu, hi = (uint32_t)codes[2 * i + 1] & 0xFu;
+        packed[i] = (uint8_t)(lo | (hi << 4));
+    }
+}
+
 }  // namespace
 
+pme_status launch_pack_int4(const int8_t* codes, int64_t pairs, uint8_t* packed, hipStream_t s) {
+    const unsigned blocks = (unsigned)std::min<int64_t>((pairs + 255) / 256, 256 * 32);
+    hipLaunchKernelGGL(k_pack_int4, dim3(blocks), dim3(256), 0, s, codes, pairs, packed);
+    return hip_status(hipGetLastError());
+}
+
 pme_status launch_gemm_generic(const GemmArgs& a) {
-    dim3 grid((unsigned)((a.N + 15) / 16), (unsigned)((a.T + 15) / 16));
-    if ((a.T + 15) / 16 > 65535) return PME_ERR_UNSUPPORTED_PATH;
+    if (a.dry) {
+        if (a.plan) *a.plan = "k_gemm_generic";
+        return PME_OK;
+    }
+    dim3 grid((unsigned)((a.N + 15) / 16), (unsigned)std::min<int64_t>((a.T + 15) / 16, 65535));
     const int kb = (int)(a.d_e / 2);
     if (a.zx)
         hipLaunchKernelGGL(k_gemm_generic<true>, grid, dim3(256), 0, a.stream, a.qx, a.qw, a.sx, a.sw, a.zx,

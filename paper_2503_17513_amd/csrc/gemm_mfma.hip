@@ -16,7 +16,8 @@
 //    int8 MFMA operands:   even codes (w & 0x0F0F0F0F) << 4,   odd codes w & 0xF0F0F0F0.
 //    A nibble moved to the top of a byte is 16 x its two's-complement value: no sign extension.
 //    Both operands carry the factor 16, the int32 accumulator holds 256 x the exact sum
-//    (|256 acc| <= 256 * 64 * d_e < 2^31 for d_e <= 2^17), removed in the epilogue.  The order in
+//    (|256 acc| <= 256 * 64 * d_e < 2^31 for d_e < 2^17; at d_e = 2^17 rows of all -8 codes would
+//    wrap, so the launcher refuses d_e >= 2^17), removed in the epilogue.  The order in
 //    which codes meet inside an MFMA is the same permutation for both operands, which an exact
 //    integer sum does not notice.
 //  * v_mfma_i32_32x32x32_i8 with the weight fragment as the first operand: a lane then owns one
@@ -25,6 +26,8 @@
 #include "pme_internal.h"
 
 #include <algorithm>
+#include <cstdio>
+#include <string>
 #include <type_traits>
 
 namespace pme {
@@ -188,7 +191,8 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
         for (int q = 0; q < PRE; ++q) {
             const int idx = tid + NT * q;
             pre[q] = 0.f;
-            if (idx < BM) pre[q] = sx[min(m0 + idx, T - 1)] * (1.f / 256.f);
+            // (the asymmetric epilogue removes the factor 256 by a shift before its zero-point correction)
+            if (idx < BM) pre[q] = sx[min(m0 + idx, T - 1)] * (MODE == MODE_ASYM ? 1.f : 1.f / 256.f);
             else if (idx < ROWS) pre[q] = sw[min(n0 + idx - BM, N - 1)];
         }
     }
@@ -507,7 +511,7 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
                 const int t = min(m0 + wm * WM + 32 * i + frow, T - 1);
                 const float sxs = sc[wm * WM + 32 * i + frow];
                 int zoff = 0;
-                if (MODE == MODE_ASYM) zoff = (zc[wm * WM + 32 * i + frow] - 8) * 256;
+                if (MODE == MODE_ASYM) zoff = zc[wm * WM + 32 * i + frow] - 8;
     #pragma unroll
                 for (int j = 0; j < FN; ++j)
     #pragma unroll
@@ -516,7 +520,9 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     #pragma unroll
                         for (int q = 0; q < 4; ++q) {
                             int a = acc[i][j][4 * eg + q];
-                            if (MODE == MODE_ASYM) a -= zoff * wsv[j][eg][q];
+                            // sum (c - 8) w - (z - 8) wsum = sum (c - z) w, at most 120 d_e in magnitude: formed
+                            // after the exact shift, so that it is not held to the x256 range
+                            if (MODE == MODE_ASYM) a = (a >> 8) - zoff * wsv[j][eg][q];
                             f[q] = (float)a * sxs * swv[j][eg][q];
                         }
                         const u32x2 pk = u32x2{pack_bf16(f[0], f[1]), pack_bf16(f[2], f[3])};
@@ -550,11 +556,28 @@ k_gemm_mfma(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
     else epilogue(std::integral_constant<int, KS - 1>{});
 }
 
+// The kernel instantiation's name as a profiler prints it (template arguments in order), per output mode.
+template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE, int KS, bool LOADER>
+const char* tile_name(int mode) {
+    auto make = [](int m) {
+        char buf[96];
+        snprintf(buf, sizeof buf, "k_gemm_mfma<%d, %d, %d, %d, %d, %d, %d, %d, %s>", BM, BN, WGM, WGN, RB, NSTAGE, m, KS,
+                 LOADER ? "true" : "false");
+        return std::string(buf);
+    };
+    static const std::string names[3] = {make(MODE_BF16), make(MODE_ASYM), make(MODE_I32)};
+    return names[mode].c_str();
+}
+
 template <int BM, int BN, int WGM, int WGN, int RB, int NSTAGE, int KS = 1, bool LOADER = false>
 pme_status launch_tile(const GemmArgs& a) {
     const int kb = (int)(a.d_e / 2);
     if (kb % 64) return PME_ERR_UNSUPPORTED_PATH;      // whole sub-steps; the last K step may be half as long
     if ((int64_t)std::max(a.T, a.N) * kb >= (int64_t(1) << 32)) return PME_ERR_UNSUPPORTED_PATH;   // 32-bit DMA offsets
+    if (a.dry) {
+        if (a.plan) *a.plan = tile_name<BM, BN, WGM, WGN, RB, NSTAGE, KS, LOADER>(a.out_i32 ? MODE_I32 : a.zx ? MODE_ASYM : MODE_BF16);
+        return PME_OK;
+    }
     const int tiles_m = (int)((a.T + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * (WGM * WGN * KS + (LOADER ? 1 : 0)));
     const size_t lds = (size_t)NSTAGE * (BM + BN) * RB;
@@ -584,8 +607,9 @@ int g_tile_override = 0;
 void set_gemm_tile_override(int id) { g_tile_override = id; }
 
 pme_status launch_gemm_mfma(const GemmArgs& a) {
-    // d_e a multiple of 128 (whole K steps), 16-byte aligned rows, and the x256 accumulator in range.
-    if (a.d_e % 128 || a.d_e > (1 << 17)) return PME_ERR_UNSUPPORTED_PATH;   // tiles with 128-byte rows need d_e % 256 == 0
+    // d_e a multiple of 128 (whole K steps), 16-byte aligned rows, and the x256 accumulator in range:
+    // 256 * 64 * d_e < 2^31 needs d_e < 2^17.
+    if (a.d_e % 128 || a.d_e >= (1 << 17)) return PME_ERR_UNSUPPORTED_PATH;   // tiles with 128-byte rows need d_e % 256 == 0
     if ((reinterpret_cast<uintptr_t>(a.qx) & 15) || (reinterpret_cast<uintptr_t>(a.qw) & 15)) return PME_ERR_UNSUPPORTED_PATH;
     if (a.zx && a.out_i32) return PME_ERR_UNSUPPORTED_PATH;
     const int64_t cus = 256;

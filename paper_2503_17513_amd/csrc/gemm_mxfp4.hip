@@ -10,6 +10,8 @@
 #include "pme_internal.h"
 
 #include <algorithm>
+#include <cstdio>
+#include <string>
 #include <type_traits>
 #include <utility>
 
@@ -328,6 +330,18 @@ pme_status launch_tile(const MxGemmArgs& a) {
     const int kb = (int)(a.d_e / 2), eb = (int)(a.d_e / 32);
     if (kb % RB) return PME_ERR_UNSUPPORTED_PATH;
     if ((int64_t)std::max(a.T, a.N) * kb >= (int64_t(1) << 32)) return PME_ERR_UNSUPPORTED_PATH;   // 32-bit DMA offsets
+    if (a.dry) {
+        if (a.plan) {
+            // the instantiation's name as a profiler prints it
+            static const std::string name = [] {
+                char buf[96];
+                snprintf(buf, sizeof buf, "k_mxgemm_mfma<%d, %d, %d, %d, %d, %d, %s>", BM, BN, WGM, WGN, RB, NSTAGE, LOADER ? "true" : "false");
+                return std::string(buf);
+            }();
+            *a.plan = name.c_str();
+        }
+        return PME_OK;
+    }
     const int tiles_m = (int)((a.T + BM - 1) / BM), tiles_n = (int)((a.N + BN - 1) / BN);
     const dim3 grid((unsigned)(tiles_m * tiles_n)), block(64 * (WGM * WGN + (LOADER ? 1 : 0)));
     const size_t lds = (size_t)NSTAGE * ((BM + BN) * RB + (BM + BN) * 4 * (RB / 64));
@@ -350,21 +364,23 @@ __global__ void __launch_bounds__(256)
 k_mxgemm_generic(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ ex, const uint8_t* __restrict__ qw,
                  const uint8_t* __restrict__ ew, int T, int N, int d_e, uint16_t* __restrict__ y, int64_t ldo) {
     const int n = blockIdx.x * 16 + (threadIdx.x & 15);
-    const int t = blockIdx.y * 16 + (threadIdx.x >> 4);
-    if (n >= N || t >= T) return;
-    const uint8_t* ar = qx + (int64_t)t * (d_e / 2);
+    if (n >= N) return;
     const uint8_t* wr = qw + (int64_t)n * (d_e / 2);
-    double sum = 0.0;
-    for (int blk = 0; blk < d_e / 32; ++blk) {
-        float inner = 0.f;      // exact: multiples of 1/4 bounded by 32 * 36
-        for (int p = 0; p < 16; ++p) {
-            const uint32_t av = ar[blk * 16 + p], wv = wr[blk * 16 + p];
-            inner += e2m1_value(av & 0xF) * e2m1_value(wv & 0xF) + e2m1_value(av >> 4) * e2m1_value(wv >> 4);
+    // blocks of 16 tokens: the grid's y extent is capped (65535), so a workgroup walks its share of them
+    for (int64_t t = (int64_t)blockIdx.y * 16 + (threadIdx.x >> 4); t < T; t += (int64_t)gridDim.y * 16) {
+        const uint8_t* ar = qx + t * (d_e / 2);
+        double sum = 0.0;
+        for (int blk = 0; blk < d_e / 32; ++blk) {
+            float inner = 0.f;      // exact: multiples of 1/4 bounded by 32 * 36
+            for (int p = 0; p < 16; ++p) {
+                const uint32_t av = ar[blk * 16 + p], wv = wr[blk * 16 + p];
+                inner += e2m1_value(av & 0xF) * e2m1_value(wv & 0xF) + e2m1_value(av >> 4) * e2m1_value(wv >> 4);
+            }
+            const int e = (int)ex[t * (d_e / 32) + blk] + (int)ew[(int64_t)n * (d_e / 32) + blk] - 254;
+            sum += ldexp((double)inner, e);
         }
-        const int e = (int)ex[(int64_t)t * (d_e / 32) + blk] + (int)ew[(int64_t)n * (d_e / 32) + blk] - 254;
-        sum += ldexp((double)inner, e);
+        y[t * ldo + n] = f32_to_bf16_bits((float)sum);
     }
-    y[(int64_t)t * ldo + n] = f32_to_bf16_bits((float)sum);
 }
 
 int g_mx_tile_override = 0;
@@ -481,8 +497,11 @@ pme_status launch_mx_decode_groups(const MxGemmArgs& a) {
 void set_mxgemm_tile_override(int id) { g_mx_tile_override = id; }
 
 pme_status launch_mxgemm_generic(const MxGemmArgs& a) {
-    if ((a.T + 15) / 16 > 65535) return PME_ERR_UNSUPPORTED_PATH;
-    dim3 grid((unsigned)((a.N + 15) / 16), (unsigned)((a.T + 15) / 16));
+    if (a.dry) {
+        if (a.plan) *a.plan = "k_mxgemm_generic";
+        return PME_OK;
+    }
+    dim3 grid((unsigned)((a.N + 15) / 16), (unsigned)std::min<int64_t>((a.T + 15) / 16, 65535));
     hipLaunchKernelGGL(k_mxgemm_generic, grid, dim3(256), 0, a.stream, a.qx, a.ex, a.qw, a.ew, (int)a.T, (int)a.N,
                        (int)a.d_e, static_cast<uint16_t*>(a.y), a.ldy);
     return hip_status(hipGetLastError());
@@ -492,6 +511,10 @@ pme_status launch_mxgemm_decode(const MxGemmArgs& a) {
     // at most 32 tokens (beyond that the tiled kernel measured faster), whole 64-byte chunks, 16-byte aligned code rows
     if (a.T > 32 || a.d_e % 128 || a.d_e > (1 << 20)) return PME_ERR_UNSUPPORTED_PATH;
     if ((reinterpret_cast<uintptr_t>(a.qx) & 15) || (reinterpret_cast<uintptr_t>(a.qw) & 15)) return PME_ERR_UNSUPPORTED_PATH;
+    if (a.dry) {
+        if (a.plan) *a.plan = "k_mxgemm_decode";
+        return PME_OK;
+    }
     if (a.T <= 16) return launch_mx_decode_groups<1>(a);
     return launch_mx_decode_groups<2>(a);
 }

@@ -4,13 +4,14 @@
 
 #include <algorithm>
 #include <atomic>
+#include <cstdio>
 
 namespace {
 
 std::atomic<int> g_path{PME_PATH_AUTO};
 
-// Base orders b = q + 1, q prime and congruent to 3 mod 4, with pairwise distinct odd parts,
-// so that d_e = b * 2^k has at most one solution.  b = 1: plain power of two.
+// Base orders b = q + 1, q a prime power congruent to 3 mod 4 (primes, and 343 = 7^3), with pairwise distinct
+// odd parts, so that d_e = b * 2^k has at most one solution.  b = 1: plain power of two.
 const int kBaseOrders[] = {1, 12, 20, 60, 68, 72, 132, 140, 152, 312, 344};
 
 bool factor_order(int64_t d_e, int* b, int* k) {
@@ -100,6 +101,51 @@ pme_status run_gemm(const pme::GemmArgs& a) {
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 
+pme_status run_mxgemm_slice(const pme::MxGemmArgs& a) {
+    int path = g_path.load();
+    if (path != PME_PATH_GENERIC) {
+        // few tokens: the weight-streaming kernel, unless the output is wide enough to fill the chip with tiles
+        const bool stream_weights = a.T <= 16 || (a.T <= 32 && a.N < 8192);
+        pme_status s = stream_weights ? pme::launch_mxgemm_decode(a) : pme::launch_mxgemm_mfma(a);
+        if (s == PME_ERR_UNSUPPORTED_PATH && stream_weights) s = pme::launch_mxgemm_mfma(a);
+        if (s != PME_ERR_UNSUPPORTED_PATH || path == PME_PATH_MFMA) return s;
+    }
+    return pme::launch_mxgemm_generic(a);
+}
+
+pme_status run_mxgemm(const pme::MxGemmArgs& a) {
+    if (a.T == 0 || a.N == 0) return PME_OK;
+    const int64_t kb = a.d_e / 2, eb = a.d_e / 32, rows = max_slice_rows(kb);
+    if (a.T <= rows && a.N <= rows) return run_mxgemm_slice(a);
+    for (int64_t t0 = 0; t0 < a.T; t0 += rows)
+        for (int64_t n0 = 0; n0 < a.N; n0 += rows) {
+            pme::MxGemmArgs p = a;
+            p.T = std::min(rows, a.T - t0);
+            p.N = std::min(rows, a.N - n0);
+            p.qx = a.qx + t0 * kb;
+            p.ex = a.ex + t0 * eb;
+            p.qw = a.qw + n0 * kb;
+            p.ew = a.ew + n0 * eb;
+            p.y = static_cast<unsigned char*>(a.y) + (t0 * a.ldy + n0) * 2;
+            const pme_status s = run_mxgemm_slice(p);
+            if (s != PME_OK) return s;
+        }
+    return PME_OK;
+}
+
+// Rotate + quantize, then the GEMM on the codes.  Both stages are asked first whether a kernel takes them (a forced
+// kernel path may refuse either), so that a refusal launches nothing.
+pme_status run_layer(const pme::RotateArgs& ra, const pme::GemmArgs& ga) {
+    pme::RotateArgs rd = ra;
+    pme::GemmArgs gd = ga;
+    rd.dry = gd.dry = true;
+    pme_status s = run_rotate(rd);
+    if (s != PME_OK) return s;
+    if ((s = run_gemm(gd)) != PME_OK) return s;
+    if ((s = run_rotate(ra)) != PME_OK) return s;
+    return run_gemm(ga);
+}
+
 }  // namespace
 
 extern "C" {
@@ -185,6 +231,41 @@ pme_status pme_weight_rowsum(const uint8_t* qw, int64_t N, int64_t d_e, int32_t*
     return pme::launch_weight_rowsum(qw, N, d_e, wsum, (hipStream_t)stream);
 }
 
+pme_status pme_pack_int4(const int8_t* codes, int64_t rows, int64_t K, uint8_t* packed, void* stream) {
+    if (rows < 0 || K < 0 || (K & 1) || rows > 0x7FFFFFFF || K > (int64_t(1) << 20)) return PME_ERR_SHAPE;
+    if (rows > 0 && K > 0 && (!codes || !packed)) return PME_ERR_NULL;
+    if (rows == 0 || K == 0) return PME_OK;
+    return pme::launch_pack_int4(codes, rows * (K / 2), packed, (hipStream_t)stream);
+}
+
+pme_status pme_gemm_plan(int variant, int64_t T, int64_t d_e, int64_t N, char* name, size_t name_len) {
+    if (!name || name_len == 0) return PME_ERR_NULL;
+    if (variant < 0 || variant > 2) return PME_ERR_DTYPE;
+    if (T <= 0 || N <= 0 || d_e <= 0 || (d_e & 1) || (variant == 2 && d_e % 32)) return PME_ERR_SHAPE;
+    if (T > 0x7FFFFFFF || N > 0x7FFFFFFF || d_e > (int64_t(1) << 20)) return PME_ERR_SHAPE;
+    // operands as the fused calls pass them: 256-byte aligned, never dereferenced by a dry run
+    const uint8_t* p8 = reinterpret_cast<const uint8_t*>(uintptr_t(256));
+    const float* pf = reinterpret_cast<const float*>(uintptr_t(256));
+    const int32_t* pi = reinterpret_cast<const int32_t*>(uintptr_t(256));
+    const char* plan = "";
+    pme_status s;
+    if (variant == 2) {
+        pme::MxGemmArgs a{p8, p8, p8, p8, T, d_e, N, const_cast<uint8_t*>(p8), N, nullptr};
+        a.dry = true;
+        a.plan = &plan;
+        s = run_mxgemm(a);
+    } else {
+        pme::GemmArgs a{p8, p8, pf, pf, variant == 1 ? pi : nullptr, variant == 1 ? pi : nullptr, T, d_e, N,
+                        const_cast<uint8_t*>(p8), N, false, nullptr};
+        a.dry = true;
+        a.plan = &plan;
+        s = run_gemm(a);
+    }
+    if (s != PME_OK) return s;
+    snprintf(name, name_len, "%s", plan);
+    return PME_OK;
+}
+
 size_t pme_workspace_bytes(int64_t T, int64_t d, int64_t d_e, int64_t N) {
     (void)N;
     if (T < 0 || d <= 0 || d_e <= 0 || d > d_e || (d_e & 1)) return 0;
@@ -212,10 +293,8 @@ pme_status pme_expanded_linear(const void* x, pme_dtype xt, int64_t T, int64_t d
     uint8_t* qx = static_cast<uint8_t*>(workspace);
     float* sx = reinterpret_cast<float*>(qx + round_up((size_t)T * (size_t)(d_e / 2), 256));
     pme::RotateArgs ra{x, xt, T, d, ldx, d_e, b, k, qx, sx, nullptr, nullptr, nullptr, (hipStream_t)stream};
-    s = run_rotate(ra);
-    if (s != PME_OK) return s;
     pme::GemmArgs ga{qx, qw, sx, sw, nullptr, nullptr, T, d_e, N, y_bf16, ldy, false, (hipStream_t)stream};
-    return run_gemm(ga);
+    return run_layer(ra, ga);
 }
 
 pme_status pme_expanded_linear_asym(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
@@ -238,10 +317,8 @@ pme_status pme_expanded_linear_asym(const void* x, pme_dtype xt, int64_t T, int6
     float* sx = reinterpret_cast<float*>(qx + round_up((size_t)T * (size_t)(d_e / 2), 256));
     int32_t* zx = reinterpret_cast<int32_t*>(reinterpret_cast<uint8_t*>(sx) + round_up(scales, 256));
     pme::RotateArgs ra{x, xt, T, d, ldx, d_e, b, k, qx, sx, zx, nullptr, nullptr, (hipStream_t)stream};
-    s = run_rotate(ra);
-    if (s != PME_OK) return s;
     pme::GemmArgs ga{qx, qw, sx, sw, zx, wsum, T, d_e, N, y_bf16, ldy, false, (hipStream_t)stream};
-    return run_gemm(ga);
+    return run_layer(ra, ga);
 }
 
 pme_status pme_hadamard_expand_quant_mxfp4(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
@@ -254,38 +331,6 @@ pme_status pme_hadamard_expand_quant_mxfp4(const void* x, pme_dtype xt, int64_t 
     if (!aligned(qx, 4)) return PME_ERR_ALIGN;
     pme::RotateArgs a{x, xt, T, d, ldx, d_e, b, k, qx, nullptr, nullptr, ex, nullptr, (hipStream_t)stream};
     return run_rotate(a);
-}
-
-static pme_status run_mxgemm_slice(const pme::MxGemmArgs& a) {
-    int path = g_path.load();
-    if (path != PME_PATH_GENERIC) {
-        // few tokens: the weight-streaming kernel, unless the output is wide enough to fill the chip with tiles
-        const bool stream_weights = a.T <= 16 || (a.T <= 32 && a.N < 8192);
-        pme_status s = stream_weights ? pme::launch_mxgemm_decode(a) : pme::launch_mxgemm_mfma(a);
-        if (s == PME_ERR_UNSUPPORTED_PATH && stream_weights) s = pme::launch_mxgemm_mfma(a);
-        if (s != PME_ERR_UNSUPPORTED_PATH || path == PME_PATH_MFMA) return s;
-    }
-    return pme::launch_mxgemm_generic(a);
-}
-
-static pme_status run_mxgemm(const pme::MxGemmArgs& a) {
-    if (a.T == 0 || a.N == 0) return PME_OK;
-    const int64_t kb = a.d_e / 2, eb = a.d_e / 32, rows = max_slice_rows(kb);
-    if (a.T <= rows && a.N <= rows) return run_mxgemm_slice(a);
-    for (int64_t t0 = 0; t0 < a.T; t0 += rows)
-        for (int64_t n0 = 0; n0 < a.N; n0 += rows) {
-            pme::MxGemmArgs p = a;
-            p.T = std::min(rows, a.T - t0);
-            p.N = std::min(rows, a.N - n0);
-            p.qx = a.qx + t0 * kb;
-            p.ex = a.ex + t0 * eb;
-            p.qw = a.qw + n0 * kb;
-            p.ew = a.ew + n0 * eb;
-            p.y = static_cast<unsigned char*>(a.y) + (t0 * a.ldy + n0) * 2;
-            const pme_status s = run_mxgemm_slice(p);
-            if (s != PME_OK) return s;
-        }
-    return PME_OK;
 }
 
 pme_status pme_mxfp4_gemm(const uint8_t* qx, const uint8_t* ex, const uint8_t* qw, const uint8_t* ew,
@@ -316,9 +361,14 @@ pme_status pme_expanded_linear_mxfp4(const void* x, pme_dtype xt, int64_t T, int
     uint8_t* qx = static_cast<uint8_t*>(workspace);
     uint8_t* ex = qx + round_up((size_t)T * (size_t)(d_e / 2), 256);
     pme::RotateArgs ra{x, xt, T, d, ldx, d_e, b, k, qx, nullptr, nullptr, ex, nullptr, (hipStream_t)stream};
+    pme::MxGemmArgs ga{qx, ex, qw, ew, T, d_e, N, y_bf16, ldy, (hipStream_t)stream};
+    // both stages are asked first whether a kernel takes them, so that a refusal launches nothing
+    pme::RotateArgs rd = ra;
+    pme::MxGemmArgs gd = ga;
+    rd.dry = gd.dry = true;
+    if ((s = run_rotate(rd)) != PME_OK || (s = run_mxgemm(gd)) != PME_OK) return s;
     s = run_rotate(ra);
     if (s != PME_OK) return s;
-    pme::MxGemmArgs ga{qx, ex, qw, ew, T, d_e, N, y_bf16, ldy, (hipStream_t)stream};
     return run_mxgemm(ga);
 }
 
@@ -362,6 +412,15 @@ pme_status pme_probe_copy(const void* src, void* dst, size_t bytes, void* stream
     if (bytes == 0) return PME_OK;
     return pme::launch_probe_copy(src, dst, bytes, (hipStream_t)stream);
 }
+
+pme_status pme_probe_read(const void* src, size_t bytes, uint32_t* sink, size_t sink_elems, void* stream) {
+    if (!src || !sink) return PME_ERR_NULL;
+    if (bytes % 16 || sink_elems < (size_t)pme::kProbeStreamBlocks * 256) return PME_ERR_SHAPE;
+    if (!aligned(src, 16) || !aligned(sink, 4)) return PME_ERR_ALIGN;
+    return pme::launch_probe_read(src, bytes, sink, (hipStream_t)stream);
+}
+
+pme_status pme_probe_launch(void* stream) { return pme::launch_probe_empty((hipStream_t)stream); }
 
 pme_status pme_probe_mfma(int kind, int32_t* out, size_t out_elems, int iters, double* ops, void* stream) {
     if (!out) return PME_ERR_NULL;

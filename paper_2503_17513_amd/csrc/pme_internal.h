@@ -22,6 +22,7 @@ struct RotateArgs {
     float* xhat;         // fp32 rotated activations out (debug) or null
     hipStream_t stream;
     int fold = 0;        // set by the MFMA launcher: butterfly stages folded into the base block (then b, k describe the folded shape)
+    bool dry = false;    // only answer whether a kernel takes the shape: nothing is launched, no table is built
 };
 
 struct MxGemmArgs {
@@ -33,6 +34,8 @@ struct MxGemmArgs {
     void* y;             // bf16 [T, ldy]
     int64_t ldy;
     hipStream_t stream;
+    bool dry = false;    // only answer whether a kernel takes the shape: nothing is launched
+    const char** plan = nullptr;   // dry runs: receives the name of the kernel configuration that would run
 };
 pme_status launch_mxgemm_generic(const MxGemmArgs& a);
 pme_status launch_mxgemm_mfma(const MxGemmArgs& a);
@@ -50,6 +53,8 @@ struct GemmArgs {
     int64_t ldy;
     bool out_i32;
     hipStream_t stream;
+    bool dry = false;    // only answer whether a kernel takes the shape: nothing is launched
+    const char** plan = nullptr;   // dry runs: receives the name of the kernel configuration that would run
 };
 
 // Each launcher returns PME_ERR_UNSUPPORTED_PATH when the shape is outside what its kernels cover.
@@ -59,7 +64,11 @@ pme_status launch_gemm_generic(const GemmArgs& a);
 pme_status launch_gemm_mfma(const GemmArgs& a);
 pme_status launch_gemm_decode(const GemmArgs& a);
 pme_status launch_weight_rowsum(const uint8_t* qw, int64_t N, int64_t d_e, int32_t* wsum, hipStream_t s);
+pme_status launch_pack_int4(const int8_t* codes, int64_t pairs, uint8_t* packed, hipStream_t s);
 pme_status launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s);
+constexpr int kProbeStreamBlocks = 256 * 8;   // workgroups of 256 threads the streaming probes launch (8 per compute unit)
+pme_status launch_probe_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s);
+pme_status launch_probe_empty(hipStream_t s);
 constexpr int kProbeMfmaBlocks = 512;   // workgroups of 256 threads the matrix-core probe launches
 pme_status launch_probe_mfma(int kind, int32_t* out, int iters, hipStream_t s);
 void set_gemm_tile_override(int id);

@@ -1,6 +1,8 @@
 // Measurement probes: kernels of known size that give the measured ceilings the hot-path kernels are
 // priced against next to the published ones, and calibrate the profiler's byte counters.
-//   k_probe_copy  plain streaming copy (HBM read + write).
+//   k_probe_copy  plain streaming copy (HBM read + write), four 16-byte loads in flight per lane.
+//   k_probe_read  read-only stream of the same shape (the rotate + quantize stage is four fifths reads).
+//   k_probe_empty a kernel that does nothing: the cost of a dependent launch, the floor of a chain of tiny kernels.
 //   k_probe_mfma  back-to-back independent matrix-core instructions with nothing else in the loop:
 //                 the rate the matrix pipe sustains at the clock the chip actually holds under that load.
 //                 That rate depends on the operands' bit activity (the pipe is power-limited), so the probe runs
@@ -11,16 +13,47 @@ namespace pme {
 namespace {
 
 typedef __attribute__((ext_vector_type(4))) int i32x4;
+typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
 typedef __attribute__((ext_vector_type(8))) int i32x8;
 typedef __attribute__((ext_vector_type(16))) int i32x16;
 typedef __attribute__((ext_vector_type(16))) float f32x16;
 
+// Each workgroup walks 16 KB pieces (4 x 16 bytes per lane, all four loads issued before the first store); the
+// chunks beyond the last whole piece are copied one per lane.
 __global__ void __launch_bounds__(256)
-k_probe_copy(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
-    size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
-    const size_t stride = (size_t)gridDim.x * 256;
-    for (; i < n16; i += stride) dst[i] = src[i];
+k_probe_copy(const u32x4* __restrict__ src, u32x4* __restrict__ dst, size_t n16) {
+    const size_t whole = n16 / 1024 * 1024;
+    for (size_t p = (size_t)blockIdx.x * 1024; p < whole; p += (size_t)gridDim.x * 1024) {
+        const size_t i = p + threadIdx.x;
+        const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + 256);
+        const u32x4 c = __builtin_nontemporal_load(src + i + 512), d = __builtin_nontemporal_load(src + i + 768);
+        __builtin_nontemporal_store(a, dst + i);
+        __builtin_nontemporal_store(b, dst + i + 256);
+        __builtin_nontemporal_store(c, dst + i + 512);
+        __builtin_nontemporal_store(d, dst + i + 768);
+    }
+    for (size_t i = whole + (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) dst[i] = src[i];
 }
+
+__global__ void __launch_bounds__(256)
+k_probe_read(const u32x4* __restrict__ src, size_t n16, uint32_t* __restrict__ sink) {
+    const size_t whole = n16 / 1024 * 1024;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    for (size_t p = (size_t)blockIdx.x * 1024; p < whole; p += (size_t)gridDim.x * 1024) {
+        const size_t i = p + threadIdx.x;
+        const u32x4 a = __builtin_nontemporal_load(src + i), b = __builtin_nontemporal_load(src + i + 256);
+        const u32x4 c = __builtin_nontemporal_load(src + i + 512), d = __builtin_nontemporal_load(src + i + 768);
+        acc.x ^= a.x ^ b.x ^ c.x ^ d.x;
+        acc.y ^= a.y ^ b.y ^ c.y ^ d.y;
+        acc.z ^= a.z ^ b.z ^ c.z ^ d.z;
+        acc.w ^= a.w ^ b.w ^ c.w ^ d.w;
+    }
+    for (size_t i = whole + (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += (size_t)gridDim.x * 256) acc.x ^= src[i].x ^ src[i].y ^ src[i].z ^ src[i].w;
+    // the result depends on every load; each lane stores it (the probe's only writes: 4 bytes per lane)
+    sink[(size_t)blockIdx.x * 256 + threadIdx.x] = acc.x ^ acc.y ^ acc.z ^ acc.w;
+}
+
+__global__ void k_probe_empty() {}
 
 __device__ __forceinline__ uint32_t probe_rand(uint32_t& state) {
     state = state * 1664525u + 1013904223u;         // a linear congruential step; the high half is the usable part
@@ -115,9 +148,19 @@ __global__ void __launch_bounds__(256) k_probe_mfma(int32_t* __restrict__ out, i
 
 pme_status launch_probe_copy(const void* src, void* dst, size_t bytes, hipStream_t s) {
     const size_t n16 = bytes / 16;
-    size_t blocks = (n16 + 255) / 256;
-    if (blocks > 256 * 16) blocks = 256 * 16;
-    hipLaunchKernelGGL(k_probe_copy, dim3((unsigned)blocks), dim3(256), 0, s, (const uint4*)src, (uint4*)dst, n16);
+    size_t blocks = (n16 + 1023) / 1024;
+    if (blocks > (size_t)kProbeStreamBlocks) blocks = kProbeStreamBlocks;
+    hipLaunchKernelGGL(k_probe_copy, dim3((unsigned)blocks), dim3(256), 0, s, (const u32x4*)src, (u32x4*)dst, n16);
+    return hip_status(hipGetLastError());
+}
+
+pme_status launch_probe_read(const void* src, size_t bytes, uint32_t* sink, hipStream_t s) {
+    hipLaunchKernelGGL(k_probe_read, dim3(kProbeStreamBlocks), dim3(256), 0, s, (const u32x4*)src, bytes / 16, sink);
+    return hip_status(hipGetLastError());
+}
+
+pme_status launch_probe_empty(hipStream_t s) {
+    hipLaunchKernelGGL(k_probe_empty, dim3(1), dim3(64), 0, s);
     return hip_status(hipGetLastError());
 }
 

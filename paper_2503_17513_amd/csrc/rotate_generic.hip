@@ -152,21 +152,19 @@ k_rotate_generic(const InT* __restrict__ x, int64_t ldx, int d, int d_e, int b, 
 pme_status launch_rotate_generic(const RotateArgs& a) {
     const size_t lds = (size_t)a.d_e * 4 + 8 * 4 + 512;      // token as fp32, reduction scratch, quadratic characters (q <= 311)
     if (lds > 160 * 1024) return PME_ERR_UNSUPPORTED_PATH;
+    if (a.dry) return PME_OK;
     const double gamma = 1.0 / sqrt((double)a.d_e);
-    hipError_t e = hipSuccess;
+    // the attribute is set once per kernel and device, to the largest size accepted above
+    static std::atomic<uint32_t> done[2];
     if (a.xt == PME_F32) {
         auto kern = k_rotate_generic<float>;
-        if (lds > 64 * 1024)
-            e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return PME_ERR_HIP;
+        if (lds > 64 * 1024 && allow_dynamic_lds(kern, 160 * 1024, done[0]) != PME_OK) return PME_ERR_HIP;
         hipLaunchKernelGGL(kern, dim3((unsigned)a.T), dim3(kThreads), lds, a.stream,
                            (const float*)a.x, a.ldx, (int)a.d, (int)a.d_e, a.b, a.k, gamma,
                            a.qx, a.sx, a.zx, a.ex, a.xhat);
     } else {
         auto kern = k_rotate_generic<uint16_t>;
-        if (lds > 64 * 1024)
-            e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return PME_ERR_HIP;
+        if (lds > 64 * 1024 && allow_dynamic_lds(kern, 160 * 1024, done[1]) != PME_OK) return PME_ERR_HIP;
         hipLaunchKernelGGL(kern, dim3((unsigned)a.T), dim3(kThreads), lds, a.stream,
                            (const uint16_t*)a.x, a.ldx, (int)a.d, (int)a.d_e, a.b, a.k, gamma,
                            a.qx, a.sx, a.zx, a.ex, a.xhat);

@@ -660,11 +660,12 @@ pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     // 160 KB per workgroup, less the kernel's static LDS rounded up to the dynamic part's 1 KB alignment
     constexpr size_t kMaxDynLds = 160 * 1024 - 1024;
     if (lds > kMaxDynLds || nwaves > max_waves<KLOG2, TPW>()) return PME_ERR_UNSUPPORTED_PATH;
+    if (KSREG > 0 && ks > KSREG) return PME_ERR_UNSUPPORTED_PATH;
+    if (a.dry) return PME_OK;
     const int rows = (int)((a.d + L::NC - 1) >> KLOG2);
     pme_status st = PME_OK;
     const Fragment* ptable = fragment_table(a.b >> a.fold, a.fold, rows, a.stream, &st);
     if (!ptable) return st;
-    if (KSREG > 0 && ks > KSREG) return PME_ERR_UNSUPPORTED_PATH;
     auto kern = k_rotate_mfma<KLOG2, TPW, F32IN, OUT, false, BGLOBAL, KSREG>;
     // the same kernel runs with different LDS sizes (they follow the shape): allow the largest one accepted above
     static std::atomic<uint32_t> done;
@@ -692,6 +693,7 @@ pme_status launch_multi_out(const RotateArgs& a, int ks) {
     const size_t lds = (size_t)kMultiWaves * ks * L::MT * 1024 + (KSREG > 0 ? 0 : (size_t)TPW * ks * 1024);
     constexpr size_t kMaxDynLds = 160 * 1024 - 1024;
     if (lds > kMaxDynLds) return PME_ERR_UNSUPPORTED_PATH;
+    if (a.dry) return PME_OK;
     const int rows = (int)((a.d + L::NC - 1) >> KLOG2);
     pme_status st = PME_OK;
     const Fragment* ptable = fragment_table(a.b >> a.fold, a.fold, rows, a.stream, &st);

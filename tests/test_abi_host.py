@@ -196,3 +196,40 @@ def test_binding_has_no_fallback():
     x = torch.zeros(2, 64)
     with pytest.raises(ValueError):
         pme.hadamard_expand_quant(x, 80)
+
+
+def test_gemm_plan_names_the_kernel_without_launching():
+    """pme_gemm_plan is a dry run of the dispatch: it needs no GPU and names the instantiation a profiler would print."""
+    assert pme.gemm_plan(4096, 15360, 4096) == "k_gemm_mfma<256, 256, 2, 2, 128, 2, 0, 1, false>"
+    assert pme.gemm_plan(4096, 15360, 4096, variant=1) == "k_gemm_mfma<256, 256, 2, 2, 128, 2, 1, 1, false>"
+    assert pme.gemm_plan(2048, 2176, 3072) == "k_gemm_mfma<128, 192, 2, 2, 64, 3, 0, 1, true>"
+    assert pme.gemm_plan(8, 8448, 2048) == "k_gemm_decode"
+    assert pme.gemm_plan(4096, 15360, 4096, variant=2).startswith("k_mxgemm_mfma<256, 256, ")
+    assert pme.gemm_plan(8, 8448, 2048, variant=2) == "k_mxgemm_decode"
+    assert pme.gemm_plan(16, 80, 64) == "k_gemm_generic"                 # d_e not a multiple of 128
+    # the x256 accumulator of the matrix-core kernels: 256 * 64 * d_e < 2^31 holds below d_e = 2^17 only
+    assert pme.gemm_plan(300, (1 << 17) - 128, 256).startswith("k_gemm_mfma<")
+    assert pme.gemm_plan(300, 1 << 17, 256) == "k_gemm_generic"
+    assert pme.gemm_plan(8, (1 << 17) - 128, 256) == "k_gemm_decode"
+    assert pme.gemm_plan(8, 1 << 17, 256) == "k_gemm_generic"
+    f = pme.lib().pme_gemm_plan
+    buf = C.create_string_buffer(64)
+    assert f(0, 8, 256, 8, None, 64) == NULL
+    assert f(3, 8, 256, 8, buf, 64) == DTYPE
+    assert f(0, 0, 256, 8, buf, 64) == SHAPE
+    assert f(0, 8, 255, 8, buf, 64) == SHAPE
+    assert f(2, 8, 80, 8, buf, 64) == SHAPE                              # MXFP4 needs whole blocks of 32
+    try:
+        pme.set_path(pme.PATH_MFMA)
+        assert f(0, 16, 80, 64, buf, 64) == PATH                         # forced matrix-core path, shape it does not take
+    finally:
+        pme.set_path(pme.PATH_AUTO)
+
+
+def test_pack_int4_argument_errors():
+    f = pme.lib().pme_pack_int4
+    assert f(None, 4, 8, FAKE, None) == NULL
+    assert f(FAKE, 4, 8, None, None) == NULL
+    assert f(FAKE, 4, 7, FAKE, None) == SHAPE
+    assert f(FAKE, -1, 8, FAKE, None) == SHAPE
+    assert f(None, 0, 8, None, None) == OK

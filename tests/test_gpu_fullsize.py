@@ -31,7 +31,7 @@ def test_full_workload(name):
     wl = make_workload(name)
     sp = wl.spec
     xd = to_device(wl.x, sp.in_dtype)
-    wd = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+    wd = pme.pack_int4(torch.from_numpy(wl.qw))
     swd = torch.from_numpy(wl.sw).cuda()
     assert pme.get_path() == pme.PATH_AUTO
     y = pme.expanded_linear(xd, sp.d_e, wd, swd)
@@ -68,7 +68,7 @@ def test_full_workload_asymmetric(name):
     wl = make_workload(name)
     sp = wl.spec
     xd = to_device(wl.x, sp.in_dtype)
-    wd = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+    wd = pme.pack_int4(torch.from_numpy(wl.qw))
     swd = torch.from_numpy(wl.sw).cuda()
     assert pme.get_path() == pme.PATH_AUTO
     wsum = pme.weight_rowsum(wd)
@@ -149,7 +149,7 @@ def test_code_matrix_beyond_4_gib():
     wl = make_workload(custom_spec(T, d, d_e, N, in_dtype="bf16", act_dist="student_t3", outlier_frac=0.02,
                                    outlier_gain=30.0, seed=11))
     xd = to_device(wl.x, "bf16")
-    wd = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+    wd = pme.pack_int4(torch.from_numpy(wl.qw))
     swd = torch.from_numpy(wl.sw).cuda()
     y = pme.expanded_linear(xd, d_e, wd, swd)
     qx, sx = pme.hadamard_expand_quant(xd, d_e)

@@ -19,6 +19,7 @@ GENERIC, MFMA = pme.PATH_GENERIC, pme.PATH_MFMA
 def _reset_path():
     yield
     pme.set_path(pme.PATH_AUTO)
+    pme.set_gemm_tile(0)
 
 
 # (name, T, d, d_e, in_dtype, paths)
@@ -322,7 +323,7 @@ def test_expanded_linear_end_to_end(name, shape):
     sp = wl.spec
     ref = oracle.expanded_linear(wl.x, sp.d_e, wl.qw, wl.sw)
     xd = to_device(wl.x, sp.in_dtype)
-    wd = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+    wd = pme.pack_int4(torch.from_numpy(wl.qw))
     assert np.array_equal(wd.cpu().numpy(), oracle.pack_int4(wl.qw))
     swd = torch.from_numpy(wl.sw).cuda()
     y = pme.expanded_linear(xd, sp.d_e, wd, swd).to(torch.float32).cpu().numpy()
@@ -352,7 +353,7 @@ def test_expanded_linear_asymmetric_end_to_end(shape):
     x = torch.from_numpy(x).to(torch.bfloat16).to(torch.float32).numpy()
     ref = oracle.expanded_linear(x, d_e, wl.qw, wl.sw, asymmetric=True)
     xd = to_device(x, "bf16")
-    wd = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+    wd = pme.pack_int4(torch.from_numpy(wl.qw))
     swd = torch.from_numpy(wl.sw).cuda()
     wsum = pme.weight_rowsum(wd)
     y = pme.expanded_linear_asym(xd, d_e, wd, swd, wsum)
@@ -397,7 +398,7 @@ def test_offline_weight_expansion_and_whole_layer_from_real_weights(d, d_e, N, d
 def test_run_twice_is_bit_identical():
     wl = make_workload(custom_spec(257, 2048, 2176, 384, seed=4))
     xd = to_device(wl.x, "bf16")
-    wd = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+    wd = pme.pack_int4(torch.from_numpy(wl.qw))
     swd = torch.from_numpy(wl.sw).cuda()
     outs = []
     for _ in range(2):
@@ -428,6 +429,104 @@ def test_forced_mfma_path_refuses_unsupported_shape():
     q = torch.zeros((4, 40), dtype=torch.uint8, device="cuda")
     with pytest.raises(pme.PmeError):
         pme.w4a4_gemm_i32(q, q)               # d_e = 80 is not a multiple of 128
+
+
+def test_pack_int4_matches_the_oracle_packing():
+    rng = np.random.default_rng(9)
+    for rows, K in ((1, 2), (7, 80), (300, 2176), (64, 15360)):
+        codes = rng.integers(-8, 8, size=(rows, K), dtype=np.int8)
+        got = pme.pack_int4(torch.from_numpy(codes)).cpu().numpy()
+        assert np.array_equal(got, oracle.pack_int4(codes))
+    assert pme.pack_int4(torch.zeros((0, 8), dtype=torch.int8)).shape == (0, 4)
+
+
+@pytest.mark.parametrize("T,tile", ((8, 0), (40, 0), (300, 8), (300, 11), (300, 16), (300, 21)),
+                         ids=("decode_kernel", "auto_small_tile", "tile_256x256_64B", "tile_256x256_128B", "tile_128x256", "tile_128x192_loader"))
+@pytest.mark.parametrize("d_e", ((1 << 17) - 128, 1 << 17), ids=("largest_matrix_core_d_e", "first_plain_alu_d_e"))
+def test_gemm_extreme_codes_either_side_of_the_accumulator_bound(T, tile, d_e):
+    """Every code -8 on both sides gives the largest sum, 64 d_e.  The matrix-core kernels hold 256 x the sum in
+    int32: 2^31 - 2^23 at d_e = 2^17 - 128, and 2^31 (a wrap) at d_e = 2^17, which therefore runs on the plain-ALU
+    kernel.  Asymmetric extremes (codes 15 with zero point 0, codes 0 with zero point 15, weights -8) reach
+    -+120 d_e after the zero-point correction, which is formed after the factor 256 has been removed.
+    Expected sums are the closed forms; the oracle supplies the epilogue."""
+    N = 272
+    big = d_e >= 1 << 17
+    if big and tile:
+        pytest.skip("the plain-ALU kernel has no tile table")
+    pme.set_gemm_tile(tile)
+    assert pme.gemm_plan(T, d_e, N).startswith("k_gemm_generic" if big else ("k_gemm_decode" if T <= 16 else "k_gemm_mfma"))
+    qx = torch.full((T, d_e // 2), 0x88, dtype=torch.uint8, device="cuda")
+    qw = torch.full((N, d_e // 2), 0x88, dtype=torch.uint8, device="cuda")
+    qx[1] = 0x77                                   # one token of all +7: the most negative sum, -56 d_e
+    acc = pme.w4a4_gemm_i32(qx, qw).cpu().numpy()
+    want = np.full((T, N), 64 * d_e, dtype=np.int64)
+    want[1] = -56 * d_e
+    assert np.array_equal(acc, want)
+    sx = torch.linspace(0.5, 1.5, T, device="cuda")
+    sw = torch.linspace(1e-3, 2e-3, N, device="cuda")
+    y = pme.w4a4_gemm(qx, sx, qw, sw).to(torch.float32).cpu().numpy()
+    check_bf16(y, oracle.dequant_bf16(want, sx.cpu().numpy(), sw.cpu().numpy()))
+    # asymmetric: unsigned codes 15 with zero point 0 (even tokens) and codes 0 with zero point 15 (odd tokens)
+    qa = torch.full((T, d_e // 2), 0xFF, dtype=torch.uint8, device="cuda")
+    qa[1::2] = 0
+    zx = torch.zeros(T, dtype=torch.int32, device="cuda")
+    zx[1::2] = 15
+    wsum = pme.weight_rowsum(qw)
+    assert np.array_equal(wsum.cpu().numpy(), np.full(N, -8 * d_e))
+    ya = pme.w4a4_gemm_asym(qa, sx, zx, qw, sw, wsum).to(torch.float32).cpu().numpy()
+    corr = np.full((T, N), -120 * d_e, dtype=np.int64)          # sum_j (15 - 0) (-8)
+    corr[1::2] = 120 * d_e                                        # sum_j (0 - 15) (-8)
+    check_bf16(ya, oracle.dequant_bf16(corr, sx.cpu().numpy(), sw.cpu().numpy()))
+
+
+def test_plain_alu_gemm_beyond_a_million_tokens():
+    """The plain-ALU kernels put blocks of 16 tokens on the grid's y axis, which ends at 65535: more tokens are
+    walked by the same workgroups.  Sampled rows around that boundary and at both ends, int4 and MXFP4."""
+    T, d_e, N = 65535 * 16 + 40, 64, 24
+    rng = np.random.default_rng(12)
+    g = torch.Generator(device="cuda").manual_seed(12)
+    qx = torch.randint(0, 256, (T, d_e // 2), dtype=torch.uint8, device="cuda", generator=g)
+    qw = torch.randint(0, 256, (N, d_e // 2), dtype=torch.uint8, device="cuda", generator=g)
+    rows = np.unique(np.concatenate([[0, 1, 65535 * 16 - 1, 65535 * 16, 65535 * 16 + 17, T - 1], rng.choice(T, 50, replace=False)]))
+    idx = torch.from_numpy(rows).cuda()
+    assert pme.gemm_plan(T, d_e, N) == "k_gemm_generic"
+    acc = pme.w4a4_gemm_i32(qx, qw)
+    assert np.array_equal(acc[idx].cpu().numpy(), oracle.int_gemm(unpack_gpu(qx[idx]), unpack_gpu(qw)))
+    ex = torch.randint(120, 130, (T, d_e // 32), dtype=torch.uint8, device="cuda", generator=g)
+    ew = torch.randint(120, 130, (N, d_e // 32), dtype=torch.uint8, device="cuda", generator=g)
+    assert pme.gemm_plan(T, d_e, N, variant=2) == "k_mxgemm_generic"
+    y = pme.mxfp4_gemm(qx, ex, qw, ew)
+    y_ref, abs_sum = oracle.gemm_mxfp4(oracle.unpack_fp4(qx[idx].cpu().numpy()), ex[idx].cpu().numpy(),
+                                       oracle.unpack_fp4(qw.cpu().numpy()), ew.cpu().numpy(), return_abs=True)
+    err = np.abs(y[idx].to(torch.float32).cpu().numpy().astype(np.float64) - y_ref)
+    assert np.all(err <= 1e-2 * np.abs(y_ref) + 2.0 ** -18 * abs_sum)
+
+
+def test_fused_layer_refused_by_a_forced_path_launches_nothing():
+    """Under the forced matrix-core path the rotation takes this shape but the GEMM does not (its weight rows are
+    only 4-byte aligned): the fused call must return the status without having run the rotation."""
+    T, d, d_e, N = 40, 2048, 2176, 64
+    x = torch.randn((T, d), device="cuda").to(torch.bfloat16)
+    store = torch.zeros((N * (d_e // 2) + 16,), dtype=torch.uint8, device="cuda")
+    qw = store[4:4 + N * (d_e // 2)].view(N, d_e // 2)
+    assert qw.data_ptr() % 16 == 4
+    sw = torch.ones(N, device="cuda")
+    ws = torch.full((pme.workspace_bytes(T, d, d_e, N),), 0xA5, dtype=torch.uint8, device="cuda")
+    y = torch.full((T, N), 3.0, dtype=torch.bfloat16, device="cuda")
+    wsum = torch.zeros(N, dtype=torch.int32, device="cuda")
+    pme.set_path(MFMA)
+    for call in (lambda: pme.expanded_linear(x, d_e, qw, sw, y, ws),
+                 lambda: pme.expanded_linear_asym(x, d_e, qw, sw, wsum, y, ws),
+                 lambda: pme.expanded_linear_mxfp4(x, d_e, qw, torch.zeros((N, d_e // 32), dtype=torch.uint8, device="cuda"), y, ws)):
+        with pytest.raises(pme.PmeError) as e:
+            call()
+        assert e.value.status == 8
+    torch.cuda.synchronize()
+    assert bool((ws == 0xA5).all()) and bool((y == 3.0).all())
+    pme.set_path(pme.PATH_AUTO)                     # the automatic path serves the same call on the plain-ALU GEMM
+    pme.expanded_linear(x, d_e, qw, sw, y, ws)
+    torch.cuda.synchronize()
+    assert not bool((ws == 0xA5).all())
 
 
 _POOL_SCRIPT = """
@@ -480,7 +579,7 @@ def test_decode_layer_calls_sharing_a_workspace():
     d, d_e, N = 8192, 8448, 1000
     wl = make_workload(custom_spec(16, d, d_e, N, act_dist="student_t3", seed=9))
     x = torch.from_numpy(wl.x).to(torch.bfloat16).cuda()
-    qw = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+    qw = pme.pack_int4(torch.from_numpy(wl.qw))
     sw = torch.from_numpy(wl.sw).cuda()
     ws = torch.empty((pme.workspace_bytes(16, d, d_e, N),), dtype=torch.uint8, device="cuda")
     for T in (16, 3, 16, 1, 8, 8):
@@ -500,7 +599,7 @@ def test_layer_in_a_hip_graph_replays_identically(shape):
     T, d, d_e, N = shape
     wl = make_workload(custom_spec(T, d, d_e, N, seed=5))
     x = torch.from_numpy(wl.x).to(torch.bfloat16).cuda()
-    qw = pme.pack_int4_codes(torch.from_numpy(wl.qw)).cuda()
+    qw = pme.pack_int4(torch.from_numpy(wl.qw))
     sw = torch.from_numpy(wl.sw).cuda()
     ws = torch.empty((pme.workspace_bytes(T, d, d_e, N),), dtype=torch.uint8, device="cuda")
     y_eager = torch.zeros((T, N), dtype=torch.bfloat16, device="cuda")
