@@ -440,8 +440,8 @@ def test_pack_int4_matches_the_oracle_packing():
     assert pme.pack_int4(torch.zeros((0, 8), dtype=torch.int8)).shape == (0, 4)
 
 
-@pytest.mark.parametrize("T,tile", ((8, 0), (40, 0), (300, 8), (300, 11), (300, 16), (300, 21)),
-                         ids=("decode_kernel", "auto_small_tile", "tile_256x256_64B", "tile_256x256_128B", "tile_128x256", "tile_128x192_loader"))
+@pytest.mark.parametrize("T,tile", ((8, 0), (40, 0), (70, 0), (300, 8), (300, 11), (300, 16), (300, 21)),
+                         ids=("decode_kernel", "decode_kernel_three_groups", "auto_small_tile", "tile_256x256_64B", "tile_256x256_128B", "tile_128x256", "tile_128x192_loader"))
 @pytest.mark.parametrize("d_e", ((1 << 17) - 128, 1 << 17), ids=("largest_matrix_core_d_e", "first_plain_alu_d_e"))
 def test_gemm_extreme_codes_either_side_of_the_accumulator_bound(T, tile, d_e):
     """Every code -8 on both sides gives the largest sum, 64 d_e.  The matrix-core kernels hold 256 x the sum in
@@ -454,7 +454,7 @@ def test_gemm_extreme_codes_either_side_of_the_accumulator_bound(T, tile, d_e):
     if big and tile:
         pytest.skip("the plain-ALU kernel has no tile table")
     pme.set_gemm_tile(tile)
-    assert pme.gemm_plan(T, d_e, N).startswith("k_gemm_generic" if big else ("k_gemm_decode" if T <= 16 else "k_gemm_mfma"))
+    assert pme.gemm_plan(T, d_e, N).startswith("k_gemm_generic" if big else ("k_gemm_decode" if T <= 64 else "k_gemm_mfma"))
     qx = torch.full((T, d_e // 2), 0x88, dtype=torch.uint8, device="cuda")
     qw = torch.full((N, d_e // 2), 0x88, dtype=torch.uint8, device="cuda")
     qx[1] = 0x77                                   # one token of all +7: the most negative sum, -56 d_e
