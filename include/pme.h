@@ -134,6 +134,24 @@ pme_status pme_expanded_linear(const void* x, pme_dtype xt, int64_t T, int64_t d
                                void* stream);
 
 /*
+ * pme_expanded_linear for callers that cannot allocate device memory or pass a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and results as
+ * pme_expanded_linear, minus the workspace: the quantized activations pass through a static array in the
+ * library's device image, PME_STATIC_SCRATCH_BYTES per GPU, held until the process ends.  The call allocates and
+ * frees nothing and enqueues the same kernels.  PME_ERR_WORKSPACE (nothing launched) if
+ * pme_workspace_bytes(T, d, d_e, N) exceeds PME_STATIC_SCRATCH_BYTES, i.e. T * d_e / 2 above roughly 16 Mi.
+ * Every call on a GPU shares that GPU's array: calls that can overlap on one GPU (different streams, or threads)
+ * race on it; calls on one stream do not.  Nothing in the array needs clearing between calls (the rotation writes
+ * all the GEMM reads).  The first call on a device looks the array's address up once, which is when the runtime
+ * places the array in that device's memory (and, like every rotation, the first call of a new shape fills its
+ * base-block table): make one call per shape before capturing a graph or entering a region that must not allocate.
+ */
+#define PME_STATIC_SCRATCH_BYTES (16u << 20)
+pme_status pme_expanded_linear_static(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                                      int64_t d_e, const uint8_t* qw, const float* sw, int64_t N,
+                                      void* y_bf16, int64_t ldy, void* stream);
+
+/*
  * The same with the paper's activation quantizer (Section 4: per-token asymmetric int4):
  * pme_hadamard_expand_quant_asym followed by pme_w4a4_gemm_asym; wsum DEVICE [N] from pme_weight_rowsum.
  * Codes, scales and zero points pass through `workspace` (same size and alignment as above).

@@ -16,7 +16,7 @@ F32, BF16 = 0, 1
 # Every symbol include/pme.h declares.
 EXPORTS = ("pme_hadamard_expand_quant", "pme_expand_quantize_weights", "pme_hadamard_expand_quant_mxfp4",
            "pme_mxfp4_gemm", "pme_expanded_linear_mxfp4", "pme_hadamard_expand_quant_asym", "pme_w4a4_gemm", "pme_w4a4_gemm_asym",
-           "pme_weight_rowsum", "pme_expanded_linear", "pme_expanded_linear_asym", "pme_workspace_bytes", "pme_hadamard_expand_f32",
+           "pme_weight_rowsum", "pme_expanded_linear", "pme_expanded_linear_static", "pme_expanded_linear_asym", "pme_workspace_bytes", "pme_hadamard_expand_f32",
            "pme_w4a4_gemm_i32", "pme_factor_order", "pme_base_block", "pme_pack_int4", "pme_gemm_plan", "pme_probe_copy", "pme_probe_read", "pme_probe_launch", "pme_probe_mfma",
            "pme_set_path", "pme_set_gemm_tile",
            "pme_get_path", "pme_status_string", "pme_version")
@@ -53,6 +53,7 @@ def lib() -> C.CDLL:
     L.pme_w4a4_gemm_i32.argtypes = [vp, vp, i64, i64, i64, vp, vp]
     L.pme_weight_rowsum.argtypes = [vp, i64, i64, vp, vp]
     L.pme_expanded_linear.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i64, vp, i64, vp, sz, vp]
+    L.pme_expanded_linear_static.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, i64, vp, i64, vp]
     L.pme_expanded_linear_asym.argtypes = [vp, i32, i64, i64, i64, i64, vp, vp, vp, i64, vp, i64, vp, sz, vp]
     L.pme_workspace_bytes.argtypes = [i64, i64, i64, i64]
     L.pme_workspace_bytes.restype = sz
@@ -303,6 +304,22 @@ def expanded_linear(x, d_e: int, qw, sw, y: torch.Tensor | None = None, workspac
                                      _dev(y, "y"), y.stride(0) if T > 1 else max(y.stride(0), N),
                                      _dev(workspace, "workspace"), workspace.numel() * workspace.element_size(),
                                      _stream()), "pme_expanded_linear")
+    return y
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def expanded_linear_static(x, d_e: int, qw, sw, y: torch.Tensor):
+    """pme_expanded_linear_static: the layer with the library's static scratch in place of a workspace; y is the
+    caller's (the call itself allocates nothing)."""
+    T, d, ldx = _rows(x)
+    N = qw.shape[0]
+    if qw.shape[1] * 2 != d_e:
+        raise ValueError("qw must be [N, d_e / 2]")
+    _check(lib().pme_expanded_linear_static(_dev(x, "x"), _dtype_code(x), T, d, ldx, d_e, _dev(qw, "qw"), _dev(sw, "sw"), N,
+                                            _dev(y, "y"), y.stride(0) if T > 1 else max(y.stride(0), N), _stream()),
+           "pme_expanded_linear_static")
     return y
 
 

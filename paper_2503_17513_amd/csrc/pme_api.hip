@@ -5,10 +5,34 @@
 #include <algorithm>
 #include <atomic>
 #include <cstdio>
+#include <mutex>
+
+// Scratch of the entry point that allocates nothing (pme_expanded_linear_static): the quantized activations pass
+// through this array instead of a caller's workspace.  Each GPU the library runs on holds its own copy until the
+// process ends.  In host code the name is only a handle for hipGetSymbolAddress, never a device address.
+static __device__ __align__(256) unsigned char scratch[PME_STATIC_SCRATCH_BYTES];
 
 namespace {
 
 std::atomic<int> g_path{PME_PATH_AUTO};
+
+// Device address of `scratch` on the current device, resolved once per device.
+constexpr int kMaxScratchDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxScratchDevices] = {};
+
+pme_status scratch_on_current_device(void** out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxScratchDevices) return PME_ERR_HIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) return PME_ERR_HIP;
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return PME_OK;
+}
 
 // Base orders b = q + 1, q a prime power congruent to 3 mod 4 (primes, and 343 = 7^3), with pairwise distinct
 // odd parts, so that d_e = b * 2^k has at most one solution.  b = 1: plain power of two.
@@ -291,6 +315,28 @@ pme_status pme_expanded_linear(const void* x, pme_dtype xt, int64_t T, int64_t d
     if (workspace_bytes < need) return PME_ERR_WORKSPACE;
     if (T == 0 || N == 0) return PME_OK;
     uint8_t* qx = static_cast<uint8_t*>(workspace);
+    float* sx = reinterpret_cast<float*>(qx + round_up((size_t)T * (size_t)(d_e / 2), 256));
+    pme::RotateArgs ra{x, xt, T, d, ldx, d_e, b, k, qx, sx, nullptr, nullptr, nullptr, (hipStream_t)stream};
+    pme::GemmArgs ga{qx, qw, sx, sw, nullptr, nullptr, T, d_e, N, y_bf16, ldy, false, (hipStream_t)stream};
+    return run_layer(ra, ga);
+}
+
+pme_status pme_expanded_linear_static(const void* x, pme_dtype xt, int64_t T, int64_t d, int64_t ldx,
+                                      int64_t d_e, const uint8_t* qw, const float* sw, int64_t N,
+                                      void* y_bf16, int64_t ldy, void* stream) {
+    int b, k;
+    pme_status s = check_rotate(x, xt, T, d, ldx, d_e, &b, &k);
+    if (s != PME_OK) return s;
+    if (N < 0 || N > 0x7FFFFFFF || ldy < N) return PME_ERR_SHAPE;
+    if (T > 0 && N > 0 && (!qw || !sw || !y_bf16)) return PME_ERR_NULL;
+    if (!aligned(qw, 4) || !aligned(sw, 4) || !aligned(y_bf16, 2)) return PME_ERR_ALIGN;
+    if (pme_workspace_bytes(T, d, d_e, N) > (size_t)PME_STATIC_SCRATCH_BYTES) return PME_ERR_WORKSPACE;
+    if (T == 0 || N == 0) return PME_OK;
+    void* base = nullptr;
+    if ((s = scratch_on_current_device(&base)) != PME_OK) return s;
+    // the same layout as the caller's workspace of pme_expanded_linear; the rotation writes every byte the GEMM
+    // reads, so nothing left by an earlier call needs clearing
+    uint8_t* qx = static_cast<uint8_t*>(base);
     float* sx = reinterpret_cast<float*>(qx + round_up((size_t)T * (size_t)(d_e / 2), 256));
     pme::RotateArgs ra{x, xt, T, d, ldx, d_e, b, k, qx, sx, nullptr, nullptr, nullptr, (hipStream_t)stream};
     pme::GemmArgs ga{qx, qw, sx, sw, nullptr, nullptr, T, d_e, N, y_bf16, ldy, false, (hipStream_t)stream};
