@@ -652,6 +652,22 @@ k_rotate_mfma(const void* __restrict__ xv, int64_t ldx, int T, int d, int d_e, i
     wait_all_vm();
 }
 
+// Workgroups of `threads` threads and `lds` bytes of dynamic LDS that one compute unit holds at once, as the runtime
+// computes it from the kernel's registers and LDS (a host-side calculation; cached per kernel for the last few
+// launch shapes).  At least 1.
+template <class K> int resident_workgroups(K kern, int threads, size_t lds) {
+    struct Entry { int threads; size_t lds; int n; };
+    static std::mutex mu;
+    static std::vector<Entry> cache;
+    std::lock_guard<std::mutex> lock(mu);
+    for (const Entry& e : cache)
+        if (e.threads == threads && e.lds == lds) return e.n;
+    int n = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&n, (const void*)kern, threads, lds) != hipSuccess || n < 1) n = 1;
+    if (cache.size() < 64) cache.push_back(Entry{threads, lds, n});
+    return n;
+}
+
 template <int KLOG2, int TPW, bool F32IN, int OUT, bool BGLOBAL = false, int KSREG = 0>
 pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     using L = Layout<KLOG2>;
@@ -677,6 +693,9 @@ pme_status launch_out(const RotateArgs& a, int ks, int nwaves) {
     int occ = (int)((160 * 1024) / (lds + 1024));
     occ = std::min(occ, (KLOG2 == 8 && nwaves == 4 ? 12 : 16) / nwaves);
     occ = std::max(1, std::min(occ, 8));
+    // never more workgroups than are resident at once (registers may admit fewer than LDS and the wave count do):
+    // a persistent grid larger than that would run in two uneven rounds
+    occ = std::min(occ, resident_workgroups(kern, 64 * nwaves, lds));
     const unsigned grid = (unsigned)std::min<int64_t>(a.T, 256 * (int64_t)occ);
     const double gamma = 1.0 / sqrt((double)a.d_e);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(64 * nwaves), lds, a.stream, a.x, a.ldx, (int)a.T, (int)a.d,
