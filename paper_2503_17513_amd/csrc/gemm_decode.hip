@@ -41,6 +41,23 @@ k_gemm_decode(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
 #pragma unroll
     for (int g = 0; g < TG; ++g) xrow[g] = qx + (int64_t)min(16 * g + r, T - 1) * kb + kg * 16;
 
+    // The epilogue's operands (thread tid < 256 finishes element tid of every group's 16 x 16 tile) are fetched now,
+    // together with the weights, so that the epilogue does not start with a dependent round trip to memory.
+    const int e_ln = (tid >> 2) & 63, e_i = tid & 3;
+    const int e_n = min(n0 + 4 * (e_ln >> 4) + e_i, N - 1);
+    float e_sw = 0.f, e_sx[TG] = {};
+    int e_ws = 0, e_zx[TG] = {};
+    if (tid < 256) {
+        if (MODE != MODE_I32) e_sw = sw[e_n];
+        if (MODE == MODE_ASYM) e_ws = wsum[e_n];
+#pragma unroll
+        for (int g = 0; g < TG; ++g) {
+            const int t = min(16 * g + (e_ln & 15), T - 1);
+            e_sx[g] = MODE != MODE_I32 ? sx[t] : 0.f;
+            e_zx[g] = MODE == MODE_ASYM ? zx[t] : 0;
+        }
+    }
+
     i32x4 acc[TG];
 #pragma unroll
     for (int g = 0; g < TG; ++g) acc[g] = i32x4{0, 0, 0, 0};
@@ -95,11 +112,11 @@ k_gemm_decode(const uint8_t* __restrict__ qx, const uint8_t* __restrict__ qw,
             s >>= 8;                                    // exact: the low 8 bits are zero
             const int t = 16 * g + (ln & 15), n = n0 + 4 * (ln >> 4) + i;
             if (t < T && n < N) {
-                if (MODE == MODE_ASYM) s -= (zx[t] - 8) * wsum[n];
+                if (MODE == MODE_ASYM) s -= (e_zx[g] - 8) * e_ws;
                 if (MODE == MODE_I32) {
                     static_cast<int32_t*>(out)[(int64_t)t * ldo + n] = s;
                 } else {
-                    const float y = (float)s * sx[t] * sw[n];
+                    const float y = (float)s * e_sx[g] * e_sw;
                     static_cast<uint16_t*>(out)[(int64_t)t * ldo + n] = f32_to_bf16_bits(y);
                 }
             }

@@ -569,8 +569,6 @@ pme_status launch_mxgemm_mfma(const MxGemmArgs& a) {
         // at 128 x 128 one wave cannot issue a stage's 40 DMA instructions in the time of its 16 matrix instructions per wave)
         case 10: return launch_tile<128, 192, 2, 2, 64, 3, true>(a);
         case 11: return launch_tile<64, 64, 2, 2, 64, 3, true>(a);
-        case 12: return launch_tile<256, 256, 2, 4, 64, 4>(a);
-        case 13: return launch_tile<256, 256, 2, 2, 64, 4>(a);
     }
     return PME_ERR_UNSUPPORTED_PATH;
 }

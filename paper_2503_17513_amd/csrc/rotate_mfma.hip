@@ -812,6 +812,9 @@ pme_status launch_rotate_mfma(const RotateArgs& in) {
             // from about 3000 tokens three tiles per wave (three waves per token, five tokens in flight per compute
             // unit) beat two (8448 .. 9728: 5-11 % at 4096 and 8192 tokens; 1-4 % slower at 2048)
             if (nt <= 16 && ks <= 4 && a.T >= 3072) return launch_one<6, 3, false, true, 4>(a, ks, (nt + 2) / 3);
+            // a handful of tokens (decode): one tile per wave, nine or ten waves per token; the kernel is a chain of
+            // latencies there and the lighter waves shorten it (8448, 8 tokens: 4.1 -> 3.8 us)
+            if (nt <= kMaxWaves && ks <= 4 && a.T <= 64) return launch_one<6, 1, false, true, 4>(a, ks, nt);
             if (nt <= 2 * kMaxWaves && ks <= 4) return launch_one<6, 2, false, true, 4>(a, ks, (nt + 1) / 2);
             // beyond 16 tiles three per wave: 7 waves for the order-312 block, so that two workgroups share a compute
             // unit (19968: 42 -> 36 us for 2048 tokens against 10 waves of two tiles)
