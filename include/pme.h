@@ -23,7 +23,8 @@
  *    stream) and returns.  One exception: the first rotation of a new shape (d, d_e) on a device fills a
  *    table of base-block fragments in library-owned device memory (a static pool of 16 MB per device, 7 to
  *    154 KB per shape, kept for the life of the process) and waits for that small kernel once; run a shape
- *    once before capturing it in a HIP graph.
+ *    once before capturing it in a HIP graph (under capture such a first call returns PME_ERR_COLD_SHAPE
+ *    and enqueues nothing).
  *  - Arguments are validated on the host before any HIP call.  A status other than
  *    PME_OK means nothing was launched (PME_ERR_HIP excepted: a launch was refused by
  *    the runtime); the fused pme_expanded_linear* calls ask both of their stages whether a
@@ -58,9 +59,13 @@ typedef enum {
     PME_ERR_WORKSPACE = 5,          /* workspace too small */
     PME_ERR_DTYPE = 6,              /* unknown pme_dtype */
     PME_ERR_HIP = 7,                /* the HIP runtime refused a launch */
-    PME_ERR_UNSUPPORTED_PATH = 8    /* no kernel path (or not the one forced with pme_set_path) runs this shape:
+    PME_ERR_UNSUPPORTED_PATH = 8,   /* no kernel path (or not the one forced with pme_set_path) runs this shape:
                                        e.g. a token of more than about 40000 expanded features whose block the
                                        matrix-core kernel does not take */
+    PME_ERR_COLD_SHAPE = 9          /* the first rotation of this shape on this device has to fill its base-block
+                                       table and wait for it, which cannot happen while `stream` is being captured
+                                       into a HIP graph: nothing was enqueued and the capture is intact; make one
+                                       call of the shape outside the capture first */
 } pme_status;
 
 typedef enum { PME_F32 = 0, PME_BF16 = 1 } pme_dtype;

@@ -1,6 +1,5 @@
-"""OCP Microscaling MXFP4 quantizer and GEMM (the paper's second quantization setting, Section 4:
-"MXFP4 for both weights and activations as specified by the Open Compute Project, which applies E8M0
-microscaling for each group of 32 elements").  Test infrastructure, fp64.
+"""OCP Microscaling MXFP4 quantizer and GEMM (the paper's second quantization setting, Section 4: OCP MXFP4
+weights and activations, one E8M0 scale per group of 32 elements).  Test infrastructure, fp64.
 
 Written from the public OCP Microscaling Formats (MX) specification v1.0:
  * element format FP4 E2M1: sign, 2 exponent bits (bias 1), 1 mantissa bit, no Inf/NaN; magnitudes by

@@ -497,6 +497,7 @@ const char* pme_status_string(pme_status s) {
         case PME_ERR_DTYPE: return "unknown dtype";
         case PME_ERR_HIP: return "HIP launch failed";
         case PME_ERR_UNSUPPORTED_PATH: return "no kernel path (or not the forced one) covers this shape";
+        case PME_ERR_COLD_SHAPE: return "first use of this shape cannot happen under stream capture";
     }
     return "unknown status";
 }

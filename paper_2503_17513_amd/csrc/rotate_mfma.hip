@@ -217,6 +217,11 @@ const Fragment* fragment_table(int b, int fold, int rows, hipStream_t stream, pm
     }
     const int tiles = ((b << fold) + 15) / 16, entries = tiles * kMaxKs;
     if (D.used + entries > kPoolEntries) { *st = PME_ERR_UNSUPPORTED_PATH; return nullptr; }
+    // The fill below is waited for, which is not allowed on a stream that is being captured into a graph (it would
+    // break the capture): refuse, leaving the capture intact.
+    hipStreamCaptureStatus capturing = hipStreamCaptureStatusNone;
+    if (hipStreamIsCapturing(stream, &capturing) != hipSuccess) { *st = PME_ERR_HIP; return nullptr; }
+    if (capturing != hipStreamCaptureStatusNone) { *st = PME_ERR_COLD_SHAPE; return nullptr; }
     Fragment* table = D.pool + D.used;
     hipLaunchKernelGGL(k_fill_ptable, dim3(entries), dim3(64), 0, stream, table, b, fold, rows);
     if (hipGetLastError() != hipSuccess || hipStreamSynchronize(stream) != hipSuccess) { *st = PME_ERR_HIP; return nullptr; }

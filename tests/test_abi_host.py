@@ -11,7 +11,7 @@ import oracle
 import paper_2503_17513_amd as pme
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-OK, NULL, SHAPE, ORDER, ALIGN, WORKSPACE, DTYPE, HIP, PATH = range(9)
+OK, NULL, SHAPE, ORDER, ALIGN, WORKSPACE, DTYPE, HIP, PATH, COLD = range(10)
 FAKE = 0x10000   # a non-null, 64 KiB aligned address that is never dereferenced: every call below fails validation
 
 
@@ -25,7 +25,7 @@ def test_header_symbols_are_exported():
         assert hasattr(L, name), name
     assert pme.version() >= 100
     assert L.pme_status_string(OK) == b"ok"
-    for s in range(1, 9):
+    for s in range(1, 10):
         assert L.pme_status_string(s) not in (b"ok", b"unknown status")
 
 

@@ -619,6 +619,47 @@ def test_layer_in_a_hip_graph_replays_identically(shape):
         assert torch.equal(y.view(torch.int16), y_eager.view(torch.int16)), f"replay {rep} differs from the eager result"
 
 
+def test_first_use_of_a_shape_under_graph_capture_is_refused_and_the_capture_survives():
+    """The first rotation of a shape fills its base-block table and waits for it once; on a capturing stream that
+    wait would break the capture, so the call returns PME_ERR_COLD_SHAPE with nothing enqueued.  After one call
+    outside a capture the same call is captured and replays with identical results."""
+    d, d_e, T = 8000, 8960, 6                       # 125 real base rows of the order-140 block: no other test uses it
+    x = (torch.randn((T, d), device="cuda") * 3).to(torch.bfloat16)
+    qx = torch.zeros((T, d_e // 2), dtype=torch.uint8, device="cuda")
+    sx = torch.zeros((T,), dtype=torch.float32, device="cuda")
+    marker = torch.zeros(8, device="cuda")
+    pme.set_path(MFMA)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    g = torch.cuda.CUDAGraph()
+    status = None
+    with torch.cuda.graph(g, stream=side):
+        marker.add_(1.0)
+        try:
+            pme.hadamard_expand_quant(x, d_e, qx, sx)
+        except pme.PmeError as e:
+            status = e.status
+    assert status == 9
+    g.replay()
+    torch.cuda.synchronize()
+    assert float(marker[0]) == 1.0 and int(qx.max()) == 0          # the captured work ran, the refused call left no trace
+    pme.hadamard_expand_quant(x, d_e, qx, sx)                       # outside a capture: fills the table
+    torch.cuda.synchronize()
+    want_q, want_s = qx.clone(), sx.clone()
+    ref_x = oracle.rotate_structured(x.to(torch.float32).cpu().numpy(), d_e)
+    q_ref, s_ref = oracle.quantize_sym_int4(ref_x)
+    check_scales(want_s.cpu().numpy(), s_ref)
+    check_codes(unpack_gpu(want_q), q_ref, ref_x, s_ref)
+    qx.zero_()
+    sx.zero_()
+    g2 = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g2, stream=side):
+        pme.hadamard_expand_quant(x, d_e, qx, sx)
+    g2.replay()
+    torch.cuda.synchronize()
+    assert torch.equal(qx, want_q) and torch.equal(sx, want_s)
+
+
 def test_probe_mfma():
     # every accumulator grows by the same amount per instruction: the checksum is linear in iters
     out = torch.zeros(512 * 256, dtype=torch.int32, device="cuda")
