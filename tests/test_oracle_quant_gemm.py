@@ -194,6 +194,24 @@ def test_expanded_linear_tracks_unquantized_layer():
     assert np.linalg.norm(ya - ref) / np.linalg.norm(ref) < 0.2
 
 
+def test_weight_quantizer_hand_example_is_per_output_channel_and_transposed():
+    """Section 4: per-channel symmetric int4 weights.  W_hat is M x N' (rows = expanded input features, columns =
+    output channels); the codes come back as one row per output channel.  Worked by hand: column 0 has absmax 3.5,
+    so its scale is 0.5 and its codes are the entries doubled; column 1 has absmax 14, scale 2, codes entries / 2
+    with 2.5 -> 2 and -0.5 -> 0 at the ties (round half to even)."""
+    What = np.array([[3.5, 14.0], [-1.0, 5.0], [0.25, -1.0], [-3.5, 3.0]])
+    q, s = oracle.quantize_weight_rtn(What)
+    assert q.shape == (2, 4) and s.shape == (2,)
+    assert np.array_equal(s, np.array([0.5, 2.0], dtype=np.float32))
+    assert np.array_equal(q[0], [7, -2, 0, -7])          # 0.25 / 0.5 = 0.5 -> 0 (tie to even)
+    assert np.array_equal(q[1], [7, 2, 0, 2])            # 2.5 -> 2, -0.5 -> -0, 1.5 -> 2
+    # a scale per column, not per row: scaling one output channel changes only that channel's scale
+    q2, s2 = oracle.quantize_weight_rtn(What * np.array([1.0, 4.0]))
+    assert np.array_equal(q2, q) and np.array_equal(s2, np.array([0.5, 8.0], dtype=np.float32))
+    # reconstruction error at most half a step per entry
+    assert np.all(np.abs(q.T * s[None, :].astype(np.float64) - What) <= 0.5 * s[None, :] + 1e-12)
+
+
 def test_c1_regression_fixture():
     with open(os.path.join(GOLD, "c1_oracle.json")) as f:
         g = json.load(f)
