@@ -60,7 +60,8 @@ def _graph_ms(fn, iters: int, repeats: int = 5):
         with torch.cuda.graph(g, stream=side):
             for _ in range(iters):
                 fn()
-        g.replay()
+        for _ in range(3):                           # untimed: clocks and caches settle before the timed replays
+            g.replay()
         torch.cuda.synchronize()
         times = []
         for _ in range(repeats):
@@ -284,7 +285,7 @@ def main() -> int:
     plain_ms = start.elapsed_time(stop) / args.steps
     # The same K steps captured once into a HIP graph and replayed: what a serving loop would do, and it
     # takes the host's launch path (a ctypes call and two kernel launches per step) out of the timed region.
-    # One untimed replay, then `replays` timed replays of exactly K steps each; the median replay is reported.
+    # Three untimed replays, then `replays` timed replays of exactly K steps each; the median replay is reported.
     ms, launch = plain_ms, "plain loop of K library calls"
     if not args.no_graph:
         g_ms = _graph_ms(step, args.steps, max(1, args.replays))
@@ -292,7 +293,7 @@ def main() -> int:
             ms, launch = g_ms, f"HIP graph of K library calls, median of {max(1, args.replays)} timed replays"
 
     ops = gemm_ops(sp)
-    iters = max(20, min(args.steps, 200))
+    iters = 100                                      # launches per graph for the per-kernel times, whatever K is
     rec, t_rot, t_gemm = workload_record(sp, b, ms, iters)
     decode = sp.T <= 32
     kernel_now = rec["gemm_kernel"]
