@@ -643,7 +643,7 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
             if (best == c256) id = wide ? 11 : 8;
             else if (best == c16) id = wide ? 16 : 2;
             else if (best == c192) id = tiles(128, 192) <= cus ? 21 : 9;     // the loader's registers allow one workgroup per unit
-            else id = 22;
+            else id = wide ? 25 : 22;   // whole 128-byte lines per K step halve the barriers of the loader tile: 3-4 % at 2048 x 2048 x 8704
         }
         // smaller outputs (measured on 18 shapes from 96 to 1536 tokens): 64 x 64, which beats 64 x 128 until the
         // latter has one and a half tiles per compute unit
@@ -678,6 +678,7 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
         case 22: return launch_tile<128, 128, 2, 2, 64, 3, 1, true>(a);    // 4 waves of 64 x 64 + loader
         case 23: return launch_tile<64, 128, 2, 2, 64, 3, 1, true>(a);     // 4 waves of 32 x 64 + loader
         case 24: return launch_tile<64, 64, 2, 2, 64, 3, 1, true>(a);      // 4 waves of 32 x 32 + loader
+        case 25: return launch_tile<128, 128, 2, 2, 128, 3, 1, true>(a);   // 4 waves of 64 x 64 + loader, 128-byte rows
     }
     return PME_ERR_UNSUPPORTED_PATH;
 }

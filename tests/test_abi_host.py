@@ -203,6 +203,7 @@ def test_gemm_plan_names_the_kernel_without_launching():
     assert pme.gemm_plan(4096, 15360, 4096) == "k_gemm_mfma<256, 256, 2, 2, 128, 2, 0, 1, false>"
     assert pme.gemm_plan(4096, 15360, 4096, variant=1) == "k_gemm_mfma<256, 256, 2, 2, 128, 2, 1, 1, false>"
     assert pme.gemm_plan(2048, 2176, 3072) == "k_gemm_mfma<128, 192, 2, 2, 64, 3, 0, 1, true>"
+    assert pme.gemm_plan(2048, 8704, 2048) == "k_gemm_mfma<128, 128, 2, 2, 128, 3, 0, 1, true>"
     assert pme.gemm_plan(8, 8448, 2048) == "k_gemm_decode"
     assert pme.gemm_plan(4096, 15360, 4096, variant=2).startswith("k_mxgemm_mfma<256, 256, ")
     assert pme.gemm_plan(8, 8448, 2048, variant=2) == "k_mxgemm_decode"
