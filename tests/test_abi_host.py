@@ -234,3 +234,24 @@ def test_pack_int4_argument_errors():
     assert f(FAKE, 4, 7, FAKE, None) == SHAPE
     assert f(FAKE, -1, 8, FAKE, None) == SHAPE
     assert f(None, 0, 8, None, None) == OK
+
+
+def test_static_scratch_layer_argument_errors():
+    """pme_expanded_linear_static validates like pme_expanded_linear and refuses, before any HIP call, a shape whose
+    quantized activations do not fit its static scratch."""
+    f = pme.lib().pme_expanded_linear_static
+
+    def call(x=FAKE, xt=1, T=8, d=8192, ldx=8192, d_e=8448, qw=FAKE, sw=FAKE, N=2048, y=FAKE, ldy=2048):
+        return f(x, xt, T, d, ldx, d_e, qw, sw, N, y, ldy, None)
+
+    assert call(x=None) == NULL
+    assert call(qw=None) == NULL
+    assert call(y=None) == NULL
+    assert call(ldy=2047) == SHAPE
+    assert call(d_e=8450) == ORDER
+    assert call(y=FAKE + 1) == ALIGN
+    assert call(T=0, x=None) == OK
+    # 4096 tokens of 15360 expanded features need 31.5 MB of codes: beyond the 16 MiB scratch
+    assert pme.workspace_bytes(4096, 14336, 15360, 4096) > pme.STATIC_SCRATCH_BYTES
+    assert call(T=4096, d=14336, ldx=14336, d_e=15360, N=4096, ldy=4096) == WORKSPACE
+    assert pme.workspace_bytes(2048, 14336, 15360, 4096) <= pme.STATIC_SCRATCH_BYTES
