@@ -647,8 +647,10 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
         }
         // smaller outputs (measured on 18 shapes from 96 to 1536 tokens): 64 x 64, which beats 64 x 128 until the
         // latter has one and a half tiles per compute unit
-        else if (tiles(64, 128) >= cus * 3 / 2) id = 23;
-        else id = 24;
+        // (with whole 128-byte lines per K step -- half the barriers -- where d_e allows: 64 x 64 another 5-13 % on four
+        // such shapes, 64 x 128 2-3 %)
+        else if (tiles(64, 128) >= cus * 3 / 2) id = wide ? 26 : 23;
+        else id = wide ? 27 : 24;
     }
     switch (id) {
         case 1: return launch_tile<256, 256, 2, 4, 64, 3>(a);      // 8 waves of 128 x 64
@@ -679,6 +681,8 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
         case 23: return launch_tile<64, 128, 2, 2, 64, 3, 1, true>(a);     // 4 waves of 32 x 64 + loader
         case 24: return launch_tile<64, 64, 2, 2, 64, 3, 1, true>(a);      // 4 waves of 32 x 32 + loader
         case 25: return launch_tile<128, 128, 2, 2, 128, 3, 1, true>(a);   // 4 waves of 64 x 64 + loader, 128-byte rows
+        case 26: return launch_tile<64, 128, 2, 2, 128, 3, 1, true>(a);    // 4 waves of 32 x 64 + loader, 128-byte rows
+        case 27: return launch_tile<64, 64, 2, 2, 128, 3, 1, true>(a);     // 4 waves of 32 x 32 + loader, 128-byte rows
     }
     return PME_ERR_UNSUPPORTED_PATH;
 }
