@@ -262,7 +262,7 @@ pme_status pme_probe_launch(void* stream);
 pme_status pme_probe_mfma(int kind, int32_t* out, size_t out_elems, int iters, double* ops, void* stream);
 
 /* Tuning hook for benchmarks: force the MFMA GEMM's tile configuration (0 = choose from the shape;
- * 1..27 = a fixed entry of the int4 kernel's tile table, 100 + (1..11) = of the MXFP4 kernel's; 0 resets
+ * 1..28 = a fixed entry of the int4 kernel's tile table, 100 + (1..11) = of the MXFP4 kernel's; 0 resets
  * both).  Process-wide, not thread-safe. */
 void pme_set_gemm_tile(int id);
 

@@ -642,7 +642,7 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
             const double best = std::min(std::min(c256, c16), std::min(c192, c128));
             if (best == c256) id = wide ? 11 : 8;
             else if (best == c16) id = wide ? 16 : 2;
-            else if (best == c192) id = tiles(128, 192) <= cus ? 21 : 9;     // the loader's registers allow one workgroup per unit
+            else if (best == c192) id = tiles(128, 192) <= cus ? (wide ? 28 : 21) : 9;     // the loader's registers allow one workgroup per unit
             else id = wide ? 25 : 22;   // whole 128-byte lines per K step halve the barriers of the loader tile: 3-4 % at 2048 x 2048 x 8704
         }
         // smaller outputs (measured on 18 shapes from 96 to 1536 tokens): 64 x 64, which beats 64 x 128 until the
@@ -683,6 +683,7 @@ pme_status launch_gemm_mfma(const GemmArgs& a) {
         case 25: return launch_tile<128, 128, 2, 2, 128, 3, 1, true>(a);   // 4 waves of 64 x 64 + loader, 128-byte rows
         case 26: return launch_tile<64, 128, 2, 2, 128, 3, 1, true>(a);    // 4 waves of 32 x 64 + loader, 128-byte rows
         case 27: return launch_tile<64, 64, 2, 2, 128, 3, 1, true>(a);     // 4 waves of 32 x 32 + loader, 128-byte rows
+        case 28: return launch_tile<128, 192, 2, 2, 128, 3, 1, true>(a);   // 4 waves of 64 x 96 + loader, 128-byte rows
     }
     return PME_ERR_UNSUPPORTED_PATH;
 }

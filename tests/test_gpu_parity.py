@@ -208,7 +208,7 @@ def test_gemm_accumulators_and_epilogue(name, T, N, d_e, paths):
 
 
 @pytest.mark.parametrize("d_e", (1280, 1152, 128))
-@pytest.mark.parametrize("tile", range(1, 28))
+@pytest.mark.parametrize("tile", range(1, 29))
 def test_gemm_every_tile_configuration(tile, d_e):
     # every entry of the MFMA kernel's tile table, forced through the tuning hook: ragged T and N; K of
     # 5 whole steps of 128 bytes, of 4.5 (a half-length last step), and of a single half step; extreme rows
@@ -260,7 +260,7 @@ def test_gemm_tile_map_is_a_bijection(tm, tn):
         assert np.array_equal(acc, acc_ref), f"tile {tile}: {np.count_nonzero(acc != acc_ref)} accumulators differ"
 
 
-@pytest.mark.parametrize("tile", (9, 11, 13, 19, 20, 21, 22, 23, 24, 25, 26, 27))
+@pytest.mark.parametrize("tile", (9, 11, 13, 19, 20, 21, 22, 23, 24, 25, 26, 27, 28))
 def test_gemm_asymmetric_on_the_default_tiles(tile):
     # the asymmetric epilogue (zero points, weight row sums) on the tiles the automatic choice uses,
     # K split included; 4.5 K steps of 128 bytes, ragged T and N
